@@ -1,0 +1,326 @@
+"""Plain fp64 CPU oracle for the Solon linear block code (encode, locate, decode).
+
+THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  Only tests, the smoke check and the
+CPU-baseline leg of the benchmark may import it.  It shares no code with the HIP
+library and imports nothing from it.  Everything is numpy in float64; inputs that
+arrive as fp32 (or bf16 widened to fp32) are widened exactly.  Nothing here is blocked,
+fused or reordered beyond what the paper's definitions state.
+
+Notation follows the paper (Sec. 3.1-3.4): P nodes, B = P per-batch gradients of
+dimension d, at most s Byzantine nodes, compression ratio m (the paper's r_c),
+message length d_c = ceil(d / m), redundancy r = 2 s + m (Thm. 2), q groups, evaluation
+points w_j, projection vector f, received matrix R = Z + N.  Arrays are stored
+row-major with one ROW per node / per batch (the paper writes them as columns).
+
+Functions and the passage each follows
+  make_plan          allocation A = I_q (x) 1_{r x r} (Sec. 3.4, "Linear Block Code"); Thm. 2 and
+                     its corollary as parameter checks; ragged groups when r does not divide P
+  default_points     "any distinct nonzero scalars" w_j (Sec. 3.4) - the values are this build's choice
+  encode             z_j = W_j Y_j 1_P with W_j = I_{d_c} (x) [1, w_j, ..., w_j^{m-1}] (Sec. 3.4)
+  project            r_{j,c} = f R_j (Sec. 3.4, definition of phi)
+  locate_bruteforce  the combinatorial definition: smallest subset S whose complement is
+                     consistent with the code (App. C, sparse-recovery equivalence)
+  locate_bw          phi: the error-locator linear system of Sec. 3.4 solved in the least-squares
+                     sense, then P_j and V = {i : P_j(w_i) != r_i} (Lemma 1, Lemma l9)
+  locate_literal     phi exactly as printed (monomial basis, P_j by polynomial division); kept
+                     only to tie locate_bw to the printed formula on tiny well-conditioned cases
+  decode             Algorithm 1 with psi = least-squares inverse of the honest rows'
+                     Vandermonde (Sec. 3.4, Lemma 2); u = sum over groups
+  plain_sum          the definition the whole mechanism must reproduce: G 1_P (Def. 1)
+
+Pins (tests/test_oracle_*.py): decode == plain_sum with zero and with <= s corrupted rows (Def. 1,
+Thm. 3); located set == planted set == brute force (Lemma 1, App. C); quotient coefficients ==
+closed form of Lemma l9; m = 1 reduces to a repetition code with majority vote; w_j = 1 gives chunk
+sums; linearity; message length of Table 2; bound tightness construction of Thm. 2's proof.
+
+Parity unpinned by the paper: the numerical thresholds (TAU, the median scale, the rank tolerance).
+The paper works over the reals ("!=", "with probability equal to unity"); these values are this
+build's reading and are pinned only by requiring brute force, locate_bw, the HIP path and the planted
+truth to coincide on every test and bench input.
+"""
+from itertools import combinations
+
+import numpy as np
+from numpy.polynomial import chebyshev as _cheb
+from numpy.polynomial import polynomial as _poly
+
+# status codes (same meaning as the C-ABI's, defined independently here)
+OK, E_INVAL, E_BOUND, E_POINTS, E_DECODE, E_NUMERIC = 0, -1, -2, -3, -4, -5
+
+TAU = 1e-4          # residual test threshold, relative to the group's median |rho|
+RANK_RCOND = 1e-10  # relative singular-value cut-off of the locator system's least-squares solve
+
+
+class OracleError(Exception):
+    def __init__(self, code, msg):
+        super().__init__(msg)
+        self.code = code
+
+
+class Plan:
+    """Immutable description of one code instance."""
+
+    def __init__(self, P, B, s, m, q, r, nodes, batches, w):
+        self.P, self.B, self.s, self.m, self.q, self.r = P, B, s, m, q, r
+        self.nodes = nodes      # list of q int arrays: node indices of each group, ascending
+        self.batches = batches  # list of q int arrays: gradient indices of each group
+        self.w = w              # float32[P]: evaluation point of every node
+
+
+def default_group_sizes(P, r):
+    """Balanced ragged blocks: q = floor(P / r) groups, the first (P mod q) one larger."""
+    q = P // r
+    base, extra = divmod(P, q)
+    return [base + 1 if g < extra else base for g in range(q)]
+
+
+def default_points(r_g):
+    """Chebyshev-type points in (-1, 1), none zero, rounded to fp32 (treated as exact afterwards).
+
+    K = 2 ceil(r_g / 2) first-kind Chebyshev nodes x_i = cos((2 i - 1) pi / (2 K)), i = 1..K;
+    for odd r_g the node with 0-based index K/2 is left out.
+    """
+    K = 2 * ((r_g + 1) // 2)
+    i = np.arange(1, K + 1, dtype=np.float64)
+    x = np.cos((2.0 * i - 1.0) * np.pi / (2.0 * K))
+    if r_g % 2 == 1:
+        x = np.delete(x, K // 2)
+    return x.astype(np.float32)
+
+
+def make_plan(P, s, m, B=None, group_of_node=None, group_of_batch=None, w=None, check_bound=True):
+    """Sec. 3.4 allocation.  Default: consecutive ragged blocks, batch k belongs to node k's group."""
+    B = P if B is None else B
+    if P < 1 or B < 1 or m < 1 or s < 0:
+        raise OracleError(E_INVAL, "bad P, B, m or s")
+    r = 2 * s + m
+    if check_bound and 2 * s > P - m:                      # corollary of Thm. 2
+        raise OracleError(E_BOUND, "s exceeds (P - m) / 2")
+    if group_of_node is None:
+        sizes = default_group_sizes(P, r)
+        group_of_node = np.repeat(np.arange(len(sizes)), sizes)
+    group_of_node = np.asarray(group_of_node, dtype=np.int64)
+    if group_of_node.shape != (P,):
+        raise OracleError(E_INVAL, "group_of_node must have P entries")
+    if group_of_batch is None:
+        if B != P:
+            raise OracleError(E_INVAL, "group_of_batch is required when B != P")
+        group_of_batch = group_of_node.copy()
+    group_of_batch = np.asarray(group_of_batch, dtype=np.int64)
+    if group_of_batch.shape != (B,):
+        raise OracleError(E_INVAL, "group_of_batch must have B entries")
+    q = int(group_of_node.max()) + 1
+    if q < 1 or group_of_node.min() < -1 or group_of_batch.min() < 0 or group_of_batch.max() >= q:
+        raise OracleError(E_INVAL, "bad group table")
+    nodes = [np.flatnonzero(group_of_node == g) for g in range(q)]
+    batches = [np.flatnonzero(group_of_batch == g) for g in range(q)]
+    for g in range(q):
+        if check_bound and len(nodes[g]) < r:              # Thm. 2: every gradient replicated >= 2s+m times
+            raise OracleError(E_BOUND, "a group has fewer than 2s+m nodes")
+    if w is None:
+        w = np.zeros(P, dtype=np.float32)
+        for g in range(q):
+            w[nodes[g]] = default_points(len(nodes[g]))
+    w = np.asarray(w, dtype=np.float32)
+    if w.shape != (P,):
+        raise OracleError(E_INVAL, "w must have P entries")
+    for g in range(q):
+        wg = w[nodes[g]]
+        if np.any(wg == 0) or not np.all(np.isfinite(wg)) or len(np.unique(wg)) != len(wg):
+            raise OracleError(E_POINTS, "evaluation points must be nonzero and distinct within a group")
+    return Plan(P, B, s, m, q, r, nodes, batches, w)
+
+
+def message_length(d, m):
+    """d_c = ceil(d / m) (Sec. 3.1: r_c = d / d_c)."""
+    return -(-d // m)
+
+
+def plain_sum(G):
+    """u = G 1_P: the sum of all per-batch gradients (Def. 1)."""
+    return np.asarray(G, dtype=np.float64).sum(axis=0)
+
+
+def encode(plan, G):
+    """All P messages.  G: [B, d] -> Z: [P, d_c] float64.  Coordinates past d read as zero."""
+    G = np.asarray(G, dtype=np.float64)
+    B, d = G.shape
+    m = plan.m
+    d_c = message_length(d, m)
+    Z = np.zeros((plan.P, d_c), dtype=np.float64)
+    for g in range(plan.q):
+        ybar = np.zeros(d_c * m, dtype=np.float64)
+        ybar[:d] = G[plan.batches[g]].sum(axis=0)          # Y_j 1_P, identical for the whole group
+        chunks = ybar.reshape(d_c, m)                      # chunk p holds coordinates p m .. p m + m - 1
+        for j in plan.nodes[g]:
+            wj = float(plan.w[j])
+            powers = np.array([wj ** l for l in range(m)], dtype=np.float64)
+            Z[j] = chunks @ powers                         # row p of W_j is [1, w_j, ..., w_j^{m-1}] on chunk p
+    return Z
+
+
+def project(R, f):
+    """rho_j = sum_p f_p R[j][p] in float64."""
+    R = np.asarray(R, dtype=np.float64)
+    f = np.asarray(f, dtype=np.float64)
+    return (R * f[None, :]).sum(axis=1)
+
+
+def _scale(y):
+    """Median magnitude of the finite projections of one group (honest nodes are a strict majority)."""
+    fin = np.abs(y[np.isfinite(y)])
+    if fin.size == 0:
+        return 0.0
+    med = float(np.median(fin))
+    if med == 0.0:
+        med = float(fin.max())
+    return med
+
+
+def _fit_and_test(wg, y, excluded, m, tau):
+    """Least-squares polynomial of degree m-1 through the points not in `excluded`;
+    returns (indices whose value differs from it by more than tau, residuals, Chebyshev coefficients)."""
+    keep = np.array([i for i in range(len(wg)) if i not in excluded], dtype=np.int64)
+    A = _cheb.chebvander(wg[keep], m - 1)
+    coef = np.linalg.lstsq(A, y[keep], rcond=None)[0]
+    res = np.abs(_cheb.chebval(wg, coef) - y)
+    flagged = [i for i in range(len(wg)) if not (res[i] <= tau)]
+    return flagged, res, coef
+
+
+def _locate_group_bruteforce(wg, rho_g, s, m, tau):
+    n = len(wg)
+    nonfinite = [i for i in range(n) if not np.isfinite(rho_g[i])]
+    sc = _scale(rho_g)
+    if sc == 0.0:
+        return nonfinite if len(nonfinite) <= s else None
+    y = np.where(np.isfinite(rho_g), rho_g / sc, 0.0)
+    for e in range(len(nonfinite), s + 1):
+        for S in combinations(range(n), e):
+            if any(i not in S for i in nonfinite):
+                continue
+            flagged, _, _ = _fit_and_test(wg, y, set(S), m, tau)
+            if all(i in S for i in flagged):
+                return sorted(S)
+    return None
+
+
+def _locator_system(wg, y, m, s):
+    """[W_{m+s-1}, -W_{s-1} .* (y 1^T)] a = y .* T_s(w): the system of Sec. 3.4 written in the
+    Chebyshev basis (a change of basis of the unknown polynomials; the locator's leading
+    Chebyshev coefficient is fixed to one), rows scaled by 1 / max(1, |y_i|)."""
+    VN = _cheb.chebvander(wg, m + s - 1)
+    VD = _cheb.chebvander(wg, s)
+    A = np.hstack([VN, -VD[:, :s] * y[:, None]])
+    b = y * VD[:, s]
+    eq = 1.0 / np.maximum(1.0, np.abs(y))
+    return A * eq[:, None], b * eq
+
+
+def _locate_group_bw(wg, rho_g, s, m, tau, want_quotient=False):
+    n = len(wg)
+    nonfinite = [i for i in range(n) if not np.isfinite(rho_g[i])]
+    if len(nonfinite) > s:
+        return None
+    sc = _scale(rho_g)
+    if sc == 0.0:
+        return (nonfinite, None) if want_quotient else nonfinite
+    fin = np.array([i for i in range(n) if i not in nonfinite], dtype=np.int64)
+    y = rho_g[fin] / sc
+    wf = wg[fin]
+    s_eff = s - len(nonfinite)                  # locator degree left for the finite entries
+    if s_eff > 0:
+        A, b = _locator_system(wf, y, m, s_eff)
+        a = np.linalg.lstsq(A, b, rcond=RANK_RCOND)[0]
+        D = np.concatenate([a[m + s_eff:], [1.0]])
+        # every corrupted point is a root of every solution's locator: the s smallest |D(w_i)|
+        absD = np.abs(_cheb.chebval(wf, D))
+        cand = set(np.argsort(absD, kind="stable")[:s_eff].tolist())
+    else:
+        cand = set()
+    # P_j: the degree-(m-1) polynomial through the remaining points (equals N / D over the reals)
+    flagged, _, coef = _fit_and_test(wf, y, cand, m, tau)
+    if len(flagged) > s_eff:
+        return None
+    V = sorted(nonfinite + [int(fin[i]) for i in flagged])
+    if want_quotient:
+        return V, _cheb.cheb2poly(coef) * sc if m > 1 else coef * sc
+    return V
+
+
+def _locate_group_literal(wg, rho_g, s, m, tau):
+    """phi as printed: monomial basis, unknowns a_1..a_{m+2s}, P_j = numerator / denominator."""
+    sc = _scale(rho_g)
+    y = rho_g / sc
+    VN = np.vander(wg, m + s, increasing=True)
+    VD = np.vander(wg, s + 1, increasing=True)
+    A = np.hstack([VN, -VD[:, :s] * y[:, None]])
+    b = y * VD[:, s]
+    a = np.linalg.lstsq(A, b, rcond=RANK_RCOND)[0]
+    num = a[:m + s]
+    den = np.concatenate([a[m + s:], [1.0]])
+    quo, _ = _poly.polydiv(num, den)
+    res = np.abs(_poly.polyval(wg, quo) - y)
+    return [i for i in range(len(wg)) if not (res[i] <= tau)], quo * sc
+
+
+def locate(plan, rho, method="bw", tau=TAU):
+    """V for all groups: sorted global node indices.  Raises OracleError(E_DECODE) when a group
+    cannot be explained by <= s corrupted nodes."""
+    rho = np.asarray(rho, dtype=np.float64)
+    V = []
+    for g in range(plan.q):
+        idx = plan.nodes[g]
+        wg = plan.w[idx].astype(np.float64)
+        if method == "bw":
+            Vg = _locate_group_bw(wg, rho[idx], plan.s, plan.m, tau)
+        elif method == "bruteforce":
+            Vg = _locate_group_bruteforce(wg, rho[idx], plan.s, plan.m, tau)
+        elif method == "literal":
+            Vg, _ = _locate_group_literal(wg, rho[idx], plan.s, plan.m, tau)
+            if len(Vg) > plan.s:
+                Vg = None
+        else:
+            raise ValueError(method)
+        if Vg is None:
+            raise OracleError(E_DECODE, "group %d: more than s inconsistent nodes" % g)
+        V.extend(int(idx[i]) for i in Vg)
+    return sorted(V)
+
+
+def quotient(plan, rho, g, method="bw", tau=TAU):
+    """Monomial coefficients (ascending) of P_j for group g - Lemma l9 says they equal
+    u_k = sum_p f_p ybar[k + p m]."""
+    idx = plan.nodes[g]
+    wg = plan.w[idx].astype(np.float64)
+    if method == "literal":
+        return _locate_group_literal(wg, np.asarray(rho, dtype=np.float64)[idx], plan.s, plan.m, tau)[1]
+    return _locate_group_bw(wg, np.asarray(rho, dtype=np.float64)[idx], plan.s, plan.m, tau, want_quotient=True)[1]
+
+
+def decode(plan, R, V, d):
+    """Algorithm 1 given the located set V (global indices): per group, psi over ALL honest nodes
+    (least-squares inverse of their m-column Vandermonde), then the sum over groups.  R: [P, d_c]."""
+    R = np.asarray(R)
+    m = plan.m
+    d_c = message_length(d, m)
+    if R.shape != (plan.P, d_c):
+        raise OracleError(E_INVAL, "R must be P x d_c")
+    Vset = set(int(v) for v in V)
+    u = np.zeros(d_c * m, dtype=np.float64)
+    for g in range(plan.q):
+        U = np.array([j for j in plan.nodes[g] if int(j) not in Vset], dtype=np.int64)
+        if len(U) < m:
+            raise OracleError(E_DECODE, "group %d: fewer than m honest nodes" % g)
+        W_U = np.vander(plan.w[U].astype(np.float64), m, increasing=True)   # [W_{m-1}]_{U,.}
+        R_U = R[U].astype(np.float64)                                       # |U| x d_c
+        coeffs = np.linalg.lstsq(W_U, R_U, rcond=None)[0]                   # m x d_c: chunk p's coefficients
+        u += coeffs.T.reshape(-1)                                           # vec(): coordinate p m + l
+    return u[:d]
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a - b))
