@@ -1,0 +1,178 @@
+"""Benchmark of the Solon hot path on one MI355X: encode -> locate -> decode per step.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--also C4] [--no-cpu-baseline]
+
+A step is one pass of the whole path over one batch of synthetic gradients that are already resident in
+HBM: solon_encode (G -> Z), solon_locate (R, f -> V, psi tables) and solon_decode (R -> u) on one stream.
+R is the encoder's output with the configuration's Byzantine rows overwritten; that harness step runs once,
+before the timed region, into its own buffer, so each timed step moves exactly the method's bytes.
+Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+
+
+def algorithmic_bytes(cfg, plan):
+    """Bytes the method must move per step on one device (each gradient read once, each message written
+    once and inspected once, m honest rows per group recombined into u)."""
+    bG = 2 if cfg["dtype"] == "bf16" else 4
+    P, d, d_c, q, m = cfg["P"], cfg["d"], plan.d_c, plan.q, cfg["m"]
+    enc = P * d * bG + P * d_c * 4
+    loc = P * d_c * 4 + d_c * 4
+    dec = q * m * d_c * 4 + d * 4
+    return dict(encode=enc, locate=loc, decode=dec, total=enc + loc + dec)
+
+
+def run_config(name, steps, warmup, want_cpu_baseline):
+    import numpy as np
+    import torch
+
+    import paper_2110_01595_amd as solon
+    import workloads
+
+    dev = torch.device("cuda:0")
+    cfg = workloads.CONFIGS[name]
+    sd = workloads.seeds(name)
+    P, s, m, d = cfg["P"], cfg["s"], cfg["m"], cfg["d"]
+    plan = solon.Plan(P, s, m, d, dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
+    d_c = plan.d_c
+    G = workloads.make_gradients(cfg, dev, sd["G"])
+    Z = torch.empty((P, d_c), dtype=torch.float32, device=dev)
+    u = torch.empty(d, dtype=torch.float32, device=dev)
+    f = workloads.make_projection(d_c, dev, sd["f"])
+    byz = workloads.pick_byzantine(P, s, sd["byz"])
+    solon.solon_encode(plan, G, Z)
+    R = Z.clone()
+    workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        solon.solon_encode(plan, G, Z)
+        if events is not None:
+            events[1].record()
+        solon.solon_locate(plan, R, f, want_host=False)
+        if events is not None:
+            events[2].record()
+        solon.solon_decode(plan, R, u)
+        if events is not None:
+            events[3].record()
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    status = solon.solon_decode_status(plan)
+    V, _ = solon.solon_locate(plan, R, f)               # after the timed region: the located set, for the record
+    ms_step = (t1 - t0) * 1e3 / steps
+    phase = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # ms
+    enc_ms, loc_ms, dec_ms = phase.mean(axis=0).tolist()
+    ab = algorithmic_bytes(cfg, plan)
+    res = dict(
+        workload=name, P=P, s=s, m=m, d=d, d_c=d_c, q=plan.q, r=plan.r, grad_dtype=cfg["dtype"], attack=cfg["attack"],
+        located_ok=(status == 0 and V == byz), ms_per_step=ms_step,
+        coords_per_s=P * d / (ms_step * 1e-3),
+        effective_GBps=ab["total"] / (ms_step * 1e-3) / 1e9,
+        phase_ms=dict(encode=enc_ms, locate=loc_ms, decode=dec_ms),
+        phase_GBps=dict(encode=ab["encode"] / enc_ms / 1e6, locate=ab["locate"] / loc_ms / 1e6, decode=ab["decode"] / dec_ms / 1e6),
+        algorithmic_bytes=ab,
+    )
+    cpu = None
+    if want_cpu_baseline:
+        cpu = cpu_baseline(cfg, plan, G, R, f, byz)
+    del G, Z, R, u, f
+    torch.cuda.empty_cache()
+    return res, cpu
+
+
+def cpu_baseline(cfg, plan, G, R, f, byz):
+    """The fp64 oracle as it stands, timed on the host on a bounded sample of the same workload:
+    the first W chunks of every row (all P nodes, all steps of the path), sized for roughly 10-30 s."""
+    import numpy as np
+    from oracle import solon_oracle as so
+
+    P, s, m = cfg["P"], cfg["s"], cfg["m"]
+    target_coords = 4.0e8                                     # P * W * m per-batch coordinates in the sample
+    W = int(min(plan.d_c, max(1024, target_coords // (P * m))))
+    dwin = min(cfg["d"], W * m)
+    Gh = G[:, :dwin].float().cpu().numpy()
+    Rh = R[:, :W].cpu().numpy()
+    fh = f[:W].cpu().numpy()
+    oplan = so.make_plan(P, s, m)
+    from threadpoolctl import threadpool_limits
+    with threadpool_limits(limits=1):                         # so that "cores" below is what actually ran
+        t0 = time.perf_counter()
+        Zo = so.encode(oplan, Gh)
+        rho = so.project(Rh, fh)
+        V = so.locate(oplan, rho)
+        uo = so.decode(oplan, Rh, V, dwin)
+        t1 = time.perf_counter()
+    ok = (V == byz) and so.rel_l2(uo, so.plain_sum(Gh)) < 1e-4 and Zo.shape == Rh.shape
+    return dict(value=P * dwin / (t1 - t0), unit="coords/s", cores=1, kind="oracle",
+                sample="first %d of %d chunks of every row (P=%d rows), one encode+project+locate+decode in %.1f s; located set %s"
+                       % (W, plan.d_c, P, t1 - t0, "matches" if ok else "MISMATCH"))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="C5")
+    ap.add_argument("--also", default="C4", help="comma-separated further workloads reported inside the same line ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the path has no collectives and every box has one GPU (--gpus %d refused)" % args.gpus)
+
+    import paper_2110_01595_amd as solon
+    solon.lib()                                              # fail loudly if the HIP library is missing
+
+    main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
+    others = []
+    for name in [n for n in args.also.split(",") if n and n != args.config]:
+        r, _ = run_config(name, args.steps, args.warmup, False)
+        others.append(r)
+
+    enc_bytes = main_res["algorithmic_bytes"]["encode"]
+    enc_s = main_res["phase_ms"]["encode"] * 1e-3
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.config, {}).get("encode_bytes_per_launch")
+    line = {
+        "metric": "encode+decode gradient coords/sec and achieved HBM GB/s (% of peak), 1 GPU",
+        "value": main_res["coords_per_s"], "unit": "coords/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.config, **{k: main_res[k] for k in ("P", "s", "m", "d", "d_c", "q", "r", "grad_dtype", "attack")}},
+        "effective_GBps": main_res["effective_GBps"], "pct_of_peak": 100.0 * main_res["effective_GBps"] / PEAK_HBM_GBS,
+        "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"], "located_ok": main_res["located_ok"],
+        "roofline": {"kernel": "encode_vec_kernel (solon_encode)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic},
+        "cpu_baseline": cpu,
+        "also": [{k: r[k] for k in ("workload", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps", "located_ok")}
+                 for r in others],
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,144 @@
+/*
+ * solon.h - C ABI of the MI355X (gfx950) implementation of Solon's linear block code:
+ * redundant-gradient encode at the compute nodes and locate + decode at the parameter server.
+ *
+ * Notation is the paper's (Sec. 3.1-3.4): P compute nodes, B per-batch gradients g_1..g_B of
+ * dimension d, at most s Byzantine nodes, compression ratio m (the paper's r_c), message length
+ * d_c = ceil(d / m), redundancy r = 2 s + m (Thm. 2), q groups ("blocks") of nodes that hold the
+ * same gradients, evaluation points w_1..w_P, projection vector f, honest messages Z, received
+ * matrix R = Z + N, located set V, decoded sum u = G 1_P.
+ *
+ * Layout.  Every matrix is row-major with one ROW per node or per batch (the paper writes nodes as
+ * columns): G is B x d, Z and R are P x d_c, contiguous along the coordinate axis, row strides given
+ * in elements.  Coordinate c of a gradient belongs to chunk p = c / m, coefficient l = c % m.
+ *
+ * Pointers.  "device" = memory of the current HIP device, "host" = ordinary host memory.  The caller
+ * owns every buffer it passes.  The library owns only the plan and the plan's small device workspace
+ * (projection partial sums, located set, recombination table), allocated once by
+ * solon_plan_create and released by solon_plan_destroy; no call allocates per invocation.
+ *
+ * Streams.  hip_stream is a hipStream_t passed as void* (NULL = the default stream).  All kernels
+ * of a call are enqueued on it in order; a call returns without waiting unless it has to hand a
+ * result back through a host pointer.  One locate -> decode pair may be in flight per plan.
+ *
+ * Errors.  Every function returns SOLON_OK or a negative solon_status; nothing throws or aborts.
+ * On error the outputs are unspecified, but no access outside the given extents is made.
+ * solon_last_error() gives a thread-local description of the last failure.
+ */
+#ifndef SOLON_H
+#define SOLON_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct solon_plan solon_plan; /* opaque; immutable after creation except for its workspace */
+
+enum solon_status {
+  SOLON_OK = 0,
+  SOLON_E_INVAL = -1,   /* null pointer, P < 1, d < 1, m < 1, s < 0, bad dtype, bad group table, bad stride,
+                           a group larger than SOLON_MAX_GROUP, 2 s + m >= SOLON_MAX_GROUP, m > 16                                             */
+  SOLON_E_BOUND = -2,   /* a group has fewer than 2 s + m nodes (Thm. 2) or s > (P - m) / 2 (its corollary) */
+  SOLON_E_POINTS = -3,  /* an evaluation point is zero, non-finite, or repeated within a group (Sec. 3.4)  */
+  SOLON_E_DECODE = -4,  /* some group cannot be explained by <= s corrupted nodes                          */
+  SOLON_E_NUMERIC = -5, /* the m x m Vandermonde chosen for psi is too ill-conditioned to invert in fp32    */
+  SOLON_E_HIP = -6      /* a HIP runtime call failed, or no device workspace exists (no GPU)                */
+};
+
+enum solon_dtype { SOLON_F32 = 0, SOLON_BF16 = 1 }; /* element type of G; Z, R, f, u are always fp32 */
+
+enum solon_query {
+  SOLON_Q_GROUPS = 0,      /* q                                                   */
+  SOLON_Q_REDUNDANCY = 1,  /* r = 2 s + m                                         */
+  SOLON_Q_MESSAGE_LEN = 2, /* d_c = ceil(d / m)                                   */
+  SOLON_Q_MAX_GROUP = 3,   /* largest group size                                  */
+  SOLON_Q_WORKSPACE = 4,   /* bytes of device workspace owned by the plan         */
+  SOLON_Q_HAS_DEVICE = 5   /* 1 if the device workspace was allocated, else 0     */
+};
+
+#define SOLON_MAX_GROUP 64 /* nodes per group handled by the single-wavefront locator */
+
+/*
+ * Allocation A and encoder weights (Sec. 3.4, "Linear Block Code": A = I_q (x) 1_{r x r},
+ * W_j = I_{d_c} (x) [1, w_j, ..., w_j^{m-1}]).  Checks Thm. 2 (every group has >= 2 s + m nodes)
+ * and its corollary (s <= (P - m) / 2).
+ *   group_of_node  host int32[P], group index of each node, or -1 for a node that takes no part;
+ *                  NULL = the default: q = floor(P / r) consecutive blocks, sizes differing by at
+ *                  most one, larger blocks first (exactly the paper's blocks when r divides P).
+ *   group_of_batch host int32[B], group whose nodes all compute gradient k; NULL = same as
+ *                  group_of_node (requires B == P and no idle node).
+ *   w              host float[P] evaluation points; NULL = Chebyshev-type points in (-1, 1),
+ *                  one set per group size (see solon_default_points).
+ * All three arrays are copied.  Creation succeeds without a GPU (host queries then work, compute
+ * calls return SOLON_E_HIP).
+ */
+int solon_plan_create(solon_plan** out, int P, int B, int s, int m, int64_t d, int grad_dtype,
+                      const int32_t* group_of_node, const int32_t* group_of_batch, const float* w);
+void solon_plan_destroy(solon_plan* plan);
+int solon_plan_query(const solon_plan* plan, int what, int64_t* value);
+/* Copies of the plan's tables into host arrays: node -> group (int32[P]) and evaluation points (float[P]). */
+int solon_plan_groups(const solon_plan* plan, int32_t* group_of_node);
+int solon_plan_points(const solon_plan* plan, float* w);
+
+/* Default evaluation points for a group of r_g nodes (host only, no GPU needed): the K = 2 ceil(r_g / 2)
+ * Chebyshev nodes cos((2 i - 1) pi / (2 K)), i = 1..K, computed in double and rounded to float; for odd r_g
+ * the node with 0-based index K / 2 is left out.  out: host float[r_g]. */
+int solon_default_points(int r_g, float* out);
+
+/*
+ * E: the messages of all P nodes (Sec. 3.4: z_j = W_j Y_j 1_P; the group sum Y_j 1_P is formed once per
+ * group and never stored).  Reads each element of G once, writes each element of Z once.
+ *   G   device, B rows x d elements of the plan's grad dtype, row stride ldg elements (ldg >= d)
+ *   Z   device, P rows x d_c fp32, row stride ldz elements (ldz >= d_c); rows of idle nodes are not written
+ * Coordinates c >= d of the last chunk count as zero.  Group sums and the Horner evaluation are fp32.
+ */
+int solon_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, void* hip_stream);
+
+/*
+ * phi for all q groups (Sec. 3.4; Lemma 1): projections rho_j = sum_p f_p R[j][p] accumulated in fp64 with
+ * a fixed reduction order, then per group the error-locator system
+ *   [W_{m+s-1}, -W_{s-1} .* (rho 1^T)] a = rho .* w^s
+ * solved in fp64 by one wavefront; nodes whose projection departs from the recovered degree-(m-1)
+ * polynomial by more than 1e-4 x (median |rho| of the group) form V.  A non-finite projection is located at once.
+ *   R        device, P x d_c fp32, row stride ldr
+ *   f        device, d_c fp32, drawn by the caller i.i.d. N(1, 1)
+ *   byz_idx  host int32[>= q * s] or NULL: receives V as ascending global node indices
+ *   n_byz    host int32* or NULL: receives |V|
+ *   rho_out  host double[P] or NULL: receives the projections
+ * V, the honest rows chosen for psi and psi's coefficient table stay in the plan's device workspace for
+ * solon_decode.  If any host output pointer is non-NULL the call waits for the stream and returns
+ * SOLON_E_DECODE / SOLON_E_NUMERIC when a group failed; with all three NULL it is asynchronous and the
+ * status is reported by solon_decode_status.
+ */
+int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const float* f, int32_t* byz_idx, int32_t* n_byz,
+                 double* rho_out, void* hip_stream);
+
+/*
+ * psi for every group and the sum over groups (Algorithm 1; Lemma 2; Thm. 3):
+ *   u[p m + l] = sum_g sum_t T[g][l][t] * R[U_g[t]][p],
+ * where U_g holds m honest nodes of group g and T[g] is the inverse of their m x m Vandermonde.
+ * Reads q * m rows of R, writes u once.
+ *   byz_idx, n_byz  host: the located set to exclude, ascending global indices; or byz_idx == NULL and
+ *                   n_byz < 0 to use what the preceding solon_locate on this plan left on the device
+ *                   (no host round trip)
+ *   u               device, d fp32
+ */
+int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
+                 void* hip_stream);
+
+/* Waits for hip_stream and returns the status the last solon_locate / solon_decode on this plan left on the
+ * device: SOLON_OK, SOLON_E_DECODE or SOLON_E_NUMERIC. */
+int solon_decode_status(solon_plan* plan, void* hip_stream);
+
+/* Launch-shape knobs for measurements (process-wide): "encode_blocks", "encode_nt", "encode_unit_mult",
+ * "encode_force_generic", "project_blocks", "decode_blocks".  Unknown keys are stored and ignored. */
+int solon_tune(const char* key, int value);
+
+const char* solon_last_error(void); /* thread-local, valid until the next failing call on this thread */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOLON_H */

@@ -1,0 +1,145 @@
+// psi for every group and the sum over groups (paper Algorithm 1, Lemma 2, Thm. 3):
+//   u[p m + l] = sum_g sum_t T[g][l][t] * R[U_g[t]][p]
+// with U_g the m honest nodes chosen for group g and T[g] the inverse of their m x m Vandermonde,
+// both left in the plan's workspace by the locator wavefront.  Reads q m rows of R once, writes u once.
+#include "solon_internal.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int CH> struct chunk_vec;
+template <> struct chunk_vec<1> { typedef float type; };
+template <> struct chunk_vec<2> { typedef f32x2 type; };
+template <> struct chunk_vec<4> { typedef f32x4 type; };
+
+// A thread owns CH consecutive chunks (CH * M output coordinates).  VEC: rows of R and u are aligned so that
+// CH-wide loads and 16-byte stores are legal.
+template <int M, int CH, bool VEC>
+__global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ rows,
+                                                         const float* __restrict__ coef, float* __restrict__ u, int64_t d,
+                                                         int64_t d_c) {
+  const int64_t nunits = (d_c + CH - 1) / CH;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; unit < nunits; unit += stride) {
+    const int64_t p = unit * CH;
+    const bool full = (p + CH <= d_c) && ((p + CH) * M <= d);
+    float out[CH * M];
+#pragma unroll
+    for (int i = 0; i < CH * M; ++i) out[i] = 0.0f;
+    for (int g = 0; g < q; ++g) {
+#pragma unroll
+      for (int t = 0; t < M; ++t) {
+        const float* src = R + (int64_t)rows[g * M + t] * ldr + p;
+        float v[CH];
+        if (VEC && full) {
+          typedef typename chunk_vec<CH>::type vt;
+          const vt x = __builtin_nontemporal_load(reinterpret_cast<const vt*>(src));
+          if constexpr (CH == 1) { v[0] = x; }
+          else if constexpr (CH == 2) { v[0] = x.x; v[1] = x.y; }
+          else { v[0] = x.x; v[1] = x.y; v[2] = x.z; v[3] = x.w; }
+        } else {
+#pragma unroll
+          for (int c = 0; c < CH; ++c) v[c] = (p + c < d_c) ? src[c] : 0.0f;
+        }
+#pragma unroll
+        for (int l = 0; l < M; ++l) {
+          const float cf = coef[(g * M + l) * M + t];
+#pragma unroll
+          for (int c = 0; c < CH; ++c) out[c * M + l] = fmaf(cf, v[c], out[c * M + l]);
+        }
+      }
+    }
+    float* dst = u + p * M;
+    if (VEC && full && (CH * M) % 4 == 0) {
+#pragma unroll
+      for (int i = 0; i < CH * M; i += 4) {
+        f32x4 x = {out[i], out[i + 1], out[i + 2], out[i + 3]};
+        __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(dst + i));
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < CH * M; ++i)
+        if (p * M + i < d) dst[i] = out[i];  // the last chunk may reach past d
+    }
+  }
+}
+
+template <int M>
+static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
+  constexpr int CH = (M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4);  // CH * M is a multiple of four
+  const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)u % 16 == 0);
+  const int64_t nunits = (plan->d_c + CH - 1) / CH;
+  const int cap = solon_tuning("decode_blocks", 16384);
+  int64_t blocks = std::min<int64_t>((nunits + 255) / 256, cap);
+  blocks = std::max<int64_t>(blocks, 1);
+  if (vec)
+    hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                       plan->dev.dec_coef, u, plan->d, plan->d_c);
+  else
+    hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                       plan->dev.dec_coef, u, plan->d, plan->d_c);
+  SOLON_HIP(hipGetLastError());
+  return SOLON_OK;
+}
+
+int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
+  switch (plan->m) {
+#define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, st);
+    SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
+    SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
+#undef SOLON_CASE
+  }
+  solon_set_error("solon_decode: no kernel for m = %d", plan->m);
+  return SOLON_E_INVAL;
+}
+
+extern "C" int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
+                            void* hip_stream) {
+  if (!plan || !R || !u) {
+    solon_set_error("solon_decode: null argument");
+    return SOLON_E_INVAL;
+  }
+  if (ldr < plan->d_c) {
+    solon_set_error("solon_decode: ldr %lld < d_c %lld", (long long)ldr, (long long)plan->d_c);
+    return SOLON_E_INVAL;
+  }
+  if (!plan->ws) {
+    solon_set_error("solon_decode: the plan has no device workspace (no GPU at creation)");
+    return SOLON_E_HIP;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  if (n_byz >= 0) {
+    // the caller names the located set: rebuild psi's tables for it on the device
+    if (n_byz > 0 && !byz_idx) {
+      solon_set_error("solon_decode: n_byz > 0 with a null index list");
+      return SOLON_E_INVAL;
+    }
+    SOLON_HIP(hipStreamSynchronize(st));  // the staging buffer may still be in use by an earlier call on this stream
+    int32_t* h_vmask = (int32_t*)plan->pinned;
+    std::vector<int> per_group(plan->q, 0);
+    for (int j = 0; j < plan->P; ++j) h_vmask[j] = 0;
+    for (int i = 0; i < n_byz; ++i) {
+      const int j = byz_idx[i];
+      if (j < 0 || j >= plan->P) {
+        solon_set_error("solon_decode: located index %d outside [0, %d)", j, plan->P);
+        return SOLON_E_INVAL;
+      }
+      if (!h_vmask[j] && plan->group_of_node[j] >= 0) per_group[plan->group_of_node[j]]++;
+      h_vmask[j] = 1;
+    }
+    for (int g = 0; g < plan->q; ++g) {
+      const int n = plan->grp_off[g + 1] - plan->grp_off[g];
+      if (n - per_group[g] < plan->m) {
+        solon_set_error("solon_decode: group %d keeps fewer than m = %d nodes", g, plan->m);
+        return SOLON_E_DECODE;
+      }
+    }
+    SOLON_HIP(hipMemcpyAsync(plan->dev.vmask, h_vmask, sizeof(int32_t) * plan->P, hipMemcpyHostToDevice, st));
+    int rc = solon_launch_solve(plan, false, st);
+    if (rc != SOLON_OK) return rc;
+  } else if (byz_idx) {
+    solon_set_error("solon_decode: n_byz < 0 requires a null index list");
+    return SOLON_E_INVAL;
+  }
+  return solon_launch_recombine(plan, R, ldr, u, st);
+}

@@ -1,0 +1,225 @@
+// Encoder of the linear block code (paper Sec. 3.4): for every group the sum of its gradients
+// Y_j 1_P is formed once in registers, and each node j of the group writes
+// z_j[p] = sum_l w_j^l * ybar[p m + l]  (row p of W_j = I_{d_c} (x) [1, w_j, .., w_j^{m-1}]).
+// One pass over G, one pass over Z; HBM-bound, no matrix cores (inner dimension <= group size).
+#include "solon_internal.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct enc_args {
+  const void* G;
+  int64_t ldg;
+  float* Z;
+  int64_t ldz;
+  int64_t d, d_c;
+  const int32_t* grp_off;
+  const int32_t* grp_nodes;
+  const int32_t* bat_off;
+  const int32_t* grp_batches;
+  const float* w;
+};
+
+__device__ __forceinline__ float elem_to_float(float v) { return v; }
+__device__ __forceinline__ float elem_to_float(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }  // bf16 widens exactly
+
+template <typename T> struct load_traits;
+template <> struct load_traits<float> { static constexpr int LV = 4; };
+template <> struct load_traits<uint16_t> { static constexpr int LV = 8; };
+
+// 16-byte load of LV consecutive elements, accumulated into acc[0..LV)
+template <bool NT>
+__device__ __forceinline__ void load_add(const float* src, float* acc) {
+  const f32x4* p = reinterpret_cast<const f32x4*>(src);
+  f32x4 v = NT ? __builtin_nontemporal_load(p) : *p;
+  acc[0] += v.x; acc[1] += v.y; acc[2] += v.z; acc[3] += v.w;
+}
+template <bool NT>
+__device__ __forceinline__ void load_add(const uint16_t* src, float* acc) {
+  const u32x4* p = reinterpret_cast<const u32x4*>(src);
+  u32x4 v = NT ? __builtin_nontemporal_load(p) : *p;
+  acc[0] += __uint_as_float(v.x << 16); acc[1] += __uint_as_float(v.x & 0xffff0000u);
+  acc[2] += __uint_as_float(v.y << 16); acc[3] += __uint_as_float(v.y & 0xffff0000u);
+  acc[4] += __uint_as_float(v.z << 16); acc[5] += __uint_as_float(v.z & 0xffff0000u);
+  acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xffff0000u);
+}
+
+template <int NC, bool NT>
+__device__ __forceinline__ void store_chunks(float* dst, const float* z) {
+  if constexpr (NC % 4 == 0) {
+#pragma unroll
+    for (int i = 0; i < NC; i += 4) {
+      f32x4 v = {z[i], z[i + 1], z[i + 2], z[i + 3]};
+      if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + i)); else *reinterpret_cast<f32x4*>(dst + i) = v;
+    }
+  } else if constexpr (NC % 2 == 0) {
+#pragma unroll
+    for (int i = 0; i < NC; i += 2) {
+      f32x2 v = {z[i], z[i + 1]};
+      if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f32x2*>(dst + i)); else *reinterpret_cast<f32x2*>(dst + i) = v;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      if (NT) __builtin_nontemporal_store(z[i], dst + i); else dst[i] = z[i];
+    }
+  }
+}
+
+// Fast path.  A thread owns UE consecutive coordinates (UE a multiple of m and of the 16-byte load width),
+// i.e. NC = UE / m whole chunks; blockIdx.y is the group.  Requires 16-byte aligned rows of G and of Z.
+template <int M, int UE, typename T, bool NT>
+__global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nunits) {
+  constexpr int LV = load_traits<T>::LV;
+  constexpr int NL = UE / LV;
+  constexpr int NC = UE / M;
+  const int g = blockIdx.y;
+  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const T* G = static_cast<const T*>(a.G);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < nunits; u += stride) {
+    float acc[UE];
+#pragma unroll
+    for (int i = 0; i < UE; ++i) acc[i] = 0.0f;
+    const T* base = G + u * UE;
+#pragma unroll 4
+    for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+      const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+#pragma unroll
+      for (int v = 0; v < NL; ++v) load_add<NT>(src + v * LV, acc + v * LV);
+    }
+    float* zbase = a.Z + u * NC;
+    for (int t = n0; t < n1; ++t) {  // one message element per node of the group and chunk
+      const int j = a.grp_nodes[t];
+      const float wj = a.w[j];
+      float z[NC];
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        float h = acc[c * M + M - 1];
+#pragma unroll
+        for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, acc[c * M + l]);  // Horner in w_j
+        z[c] = h;
+      }
+      store_chunks<NC, NT>(zbase + (int64_t)j * a.ldz, z);
+    }
+  }
+}
+
+// General path: any alignment, any d; a thread owns one chunk p in [p0, p1).
+template <int M, typename T>
+__global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p0, int64_t p1) {
+  const int g = blockIdx.y;
+  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const T* G = static_cast<const T*>(a.G);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t p = p0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < p1; p += stride) {
+    float y[M];
+#pragma unroll
+    for (int l = 0; l < M; ++l) y[l] = 0.0f;
+    for (int k = b0; k < b1; ++k) {
+      const T* src = G + (int64_t)a.grp_batches[k] * a.ldg + p * M;
+#pragma unroll
+      for (int l = 0; l < M; ++l)
+        if (p * M + l < a.d) y[l] += elem_to_float(src[l]);  // coordinates past d count as zero
+    }
+    for (int t = n0; t < n1; ++t) {
+      const int j = a.grp_nodes[t];
+      const float wj = a.w[j];
+      float h = y[M - 1];
+#pragma unroll
+      for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);
+      a.Z[(int64_t)j * a.ldz + p] = h;
+    }
+  }
+}
+
+static constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
+static constexpr int lcm_c(int a, int b) { return a / gcd_c(a, b) * b; }
+
+template <int M, typename T>
+static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool aligned, hipStream_t st) {
+  constexpr int LV = load_traits<T>::LV;
+  constexpr int UE = lcm_c(M, LV);
+  const int threads = 256;
+  const int q = plan->q;
+  const int cap = solon_tuning("encode_blocks", 8192);  // total blocks of the grid-stride launch
+  const bool nt = solon_tuning("encode_nt", 1) != 0;
+  const int mult = (M == 1 || M == 2 || M == 4) ? solon_tuning("encode_unit_mult", 1) : 1;
+  int64_t done_chunks = 0;
+  if (aligned && solon_tuning("encode_force_generic", 0) == 0) {
+    const int ue = UE * mult;
+    const int64_t nunits = plan->d / ue;
+    if (nunits > 0) {
+      int64_t bx = (nunits + threads - 1) / threads;
+      bx = std::min<int64_t>(bx, std::max(1, cap / q));
+      dim3 grid((unsigned)bx, (unsigned)q);
+#define SOLON_ENC_LAUNCH(UEV)                                                                               \
+  do {                                                                                                      \
+    if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, UEV, T, true>), grid, dim3(threads), 0, st, a, nunits); \
+    else hipLaunchKernelGGL((encode_vec_kernel<M, UEV, T, false>), grid, dim3(threads), 0, st, a, nunits);   \
+  } while (0)
+      if constexpr (M == 1 || M == 2 || M == 4) {
+        if (mult == 4) SOLON_ENC_LAUNCH(UE * 4);
+        else if (mult == 2) SOLON_ENC_LAUNCH(UE * 2);
+        else SOLON_ENC_LAUNCH(UE);
+      } else {
+        SOLON_ENC_LAUNCH(UE);
+      }
+#undef SOLON_ENC_LAUNCH
+      SOLON_HIP(hipGetLastError());
+      done_chunks = nunits * (ue / M);
+    }
+  }
+  if (done_chunks < plan->d_c) {  // ragged tail, or the whole range when rows are not 16-byte aligned
+    const int64_t n = plan->d_c - done_chunks;
+    int64_t bx = (n + threads - 1) / threads;
+    bx = std::min<int64_t>(bx, std::max(1, cap / q));
+    hipLaunchKernelGGL((encode_chunk_kernel<M, T>), dim3((unsigned)bx, (unsigned)q), dim3(threads), 0, st, a, done_chunks,
+                       plan->d_c);
+    SOLON_HIP(hipGetLastError());
+  }
+  return SOLON_OK;
+}
+
+template <typename T>
+static int encode_by_m(const solon_plan* plan, const enc_args& a, bool aligned, hipStream_t st) {
+  switch (plan->m) {
+#define SOLON_CASE(MV) case MV: return encode_dispatch<MV, T>(plan, a, aligned, st);
+    SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
+    SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
+#undef SOLON_CASE
+  }
+  solon_set_error("solon_encode: no kernel for m = %d", plan->m);
+  return SOLON_E_INVAL;
+}
+
+int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st) {
+  enc_args a;
+  a.G = G; a.ldg = ldg; a.Z = Z; a.ldz = ldz; a.d = plan->d; a.d_c = plan->d_c;
+  a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes;
+  a.bat_off = plan->dev.bat_off; a.grp_batches = plan->dev.grp_batches; a.w = plan->dev.w;
+  const size_t esz = plan->dtype == SOLON_BF16 ? 2 : 4;
+  const bool aligned = ((uintptr_t)G % 16 == 0) && ((size_t)ldg * esz % 16 == 0) && ((uintptr_t)Z % 16 == 0) && (ldz % 4 == 0);
+  if (plan->dtype == SOLON_BF16) return encode_by_m<uint16_t>(plan, a, aligned, st);
+  return encode_by_m<float>(plan, a, aligned, st);
+}
+
+extern "C" int solon_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, void* hip_stream) {
+  if (!plan || !G || !Z) {
+    solon_set_error("solon_encode: null argument");
+    return SOLON_E_INVAL;
+  }
+  if (ldg < plan->d || ldz < plan->d_c) {
+    solon_set_error("solon_encode: row stride smaller than the row length (ldg %lld < d %lld or ldz %lld < d_c %lld)",
+                    (long long)ldg, (long long)plan->d, (long long)ldz, (long long)plan->d_c);
+    return SOLON_E_INVAL;
+  }
+  if (!plan->ws) {
+    solon_set_error("solon_encode: the plan has no device workspace (no GPU at creation)");
+    return SOLON_E_HIP;
+  }
+  return solon_launch_encode(plan, G, ldg, Z, ldz, (hipStream_t)hip_stream);
+}

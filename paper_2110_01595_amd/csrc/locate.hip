@@ -1,0 +1,466 @@
+// phi of the linear block code (paper Sec. 3.4, Lemma 1, Lemma l9) for all groups:
+//   1. rho_j = f R_j, accumulated in fp64 with a fixed reduction tree (project_kernel + reduce_kernel);
+//   2. per group, one wavefront builds and solves the error-locator system
+//        [W_{m+s-1}, -W_{s-1} .* (rho 1^T)] a = rho .* w^s
+//      (written in the Chebyshev basis, rows equilibrated), takes the s points where the locator
+//      polynomial is smallest as root candidates, refits the degree-(m-1) polynomial P_j through the
+//      other points and flags V = {i : |P_j(w_i) - rho_i| > tau * median|rho|};
+//   3. the same wavefront prepares psi (Lemma 2): m well-spread honest nodes of the group and the
+//      inverse of their m x m Vandermonde (Lagrange basis coefficients), left on the device for decode.
+#include <math.h>
+
+#include "solon_internal.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+#define SOLON_TAU 1e-4          // residual threshold relative to the group's median |rho|
+#define SOLON_RANK_TOL 1e-12    // a column whose remaining norm falls below this fraction is dependent
+#define SOLON_INV_NORM_MAX 1e6  // largest accepted infinity norm of the inverse m x m Vandermonde
+
+// ------------------------------------------------------------------------------------------------
+// Projection.  grid = (row bunches, column tiles); a thread keeps one fp64 accumulator per row of its
+// bunch and walks its tile's columns with 16-byte loads, so f is loaded once per RB rows of R.
+template <int RB, bool VEC>
+__global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ R, int64_t ldr, const float* __restrict__ f,
+                                                       int64_t d_c, int P, int rows_per_bunch, double* __restrict__ partials) {
+  const int bunch = blockIdx.x, tile = blockIdx.y, ntiles = gridDim.y;
+  const int row0 = bunch * rows_per_bunch;
+  const int nrows = min(rows_per_bunch, P - row0);
+  const int tid = threadIdx.x;
+  double acc[RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i) acc[i] = 0.0;
+  const float* Rb = R + (int64_t)row0 * ldr;
+  if (VEC) {
+    const int64_t nvec = d_c / 4;
+    for (int64_t u = (int64_t)tile * 256 + tid; u < nvec; u += (int64_t)ntiles * 256) {
+      const f32x4 fv = *reinterpret_cast<const f32x4*>(f + 4 * u);
+      const double f0 = fv.x, f1 = fv.y, f2 = fv.z, f3 = fv.w;
+#pragma unroll
+      for (int i = 0; i < RB; ++i) {
+        if (i < nrows) {
+          const f32x4 rv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Rb + (int64_t)i * ldr + 4 * u));
+          acc[i] = fma(f0, (double)rv.x, acc[i]);
+          acc[i] = fma(f1, (double)rv.y, acc[i]);
+          acc[i] = fma(f2, (double)rv.z, acc[i]);
+          acc[i] = fma(f3, (double)rv.w, acc[i]);
+        }
+      }
+    }
+    if (tile == 0 && tid < (int)(d_c - nvec * 4)) {  // fewer than four trailing columns
+      const int64_t c = nvec * 4 + tid;
+      const double fc = f[c];
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+        if (i < nrows) acc[i] = fma(fc, (double)Rb[(int64_t)i * ldr + c], acc[i]);
+    }
+  } else {
+    for (int64_t c = (int64_t)tile * 256 + tid; c < d_c; c += (int64_t)ntiles * 256) {
+      const double fc = f[c];
+#pragma unroll
+      for (int i = 0; i < RB; ++i)
+        if (i < nrows) acc[i] = fma(fc, (double)Rb[(int64_t)i * ldr + c], acc[i]);
+    }
+  }
+  // fixed-order reduction: butterfly inside each wavefront, then the four wavefronts in order
+  __shared__ double sm[4][RB];
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int i = 0; i < RB; ++i) {
+    double v = acc[i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    if (lane == 0) sm[wave][i] = v;
+  }
+  __syncthreads();
+  if (tid < nrows) partials[(int64_t)tile * P + row0 + tid] = ((sm[0][tid] + sm[1][tid]) + sm[2][tid]) + sm[3][tid];
+}
+
+// rho_j = sum over tiles of partials[tile][j], one wavefront per node, fixed order.
+__global__ __launch_bounds__(64) void reduce_kernel(const double* __restrict__ partials, int ntiles, int P, double* __restrict__ rho) {
+  const int j = blockIdx.x, lane = threadIdx.x;
+  double v = 0.0;
+  for (int t = lane; t < ntiles; t += 64) v += partials[(int64_t)t * P + j];
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  if (lane == 0) rho[j] = v;
+}
+
+int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
+  const int P = plan->P;
+  const int nbunch = (P + SOLON_PROJ_ROWS - 1) / SOLON_PROJ_ROWS;
+  const int rows_per_bunch = (P + nbunch - 1) / nbunch;
+  const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
+  const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
+  const int cap = solon_tuning("project_blocks", 4096);
+  int64_t ntiles = std::max<int64_t>(1, (work + 255) / 256);
+  ntiles = std::min<int64_t>(ntiles, std::max(1, cap / nbunch));
+  ntiles = std::min<int64_t>(ntiles, SOLON_PROJ_MAX_TILES);
+  plan->proj_tiles = (int)ntiles;
+  dim3 grid((unsigned)nbunch, (unsigned)ntiles);
+  if (vec)
+    hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, true>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
+                       plan->dev.partials);
+  else
+    hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, false>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
+                       plan->dev.partials);
+  SOLON_HIP(hipGetLastError());
+  hipLaunchKernelGGL(reduce_kernel, dim3(P), dim3(64), 0, st, plan->dev.partials, (int)ntiles, P, plan->dev.rho);
+  SOLON_HIP(hipGetLastError());
+  return SOLON_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Single-wavefront solve.  Lane i stands for point i of the group when evaluating polynomials and for
+// column i of the system when applying Householder reflections.
+#define LDA 66
+struct solve_smem {
+  double A[64][LDA];  // system matrix, right-hand side in column nc
+  double x[64];       // solution
+  double cn[64];      // initial column norms
+  double y[64];       // normalised projections of the finite points
+  double wv[64];      // their evaluation points
+  double val[64];     // scratch values compared across lanes
+  double lag[SOLON_MAX_M][SOLON_MAX_M + 1];
+  double med[2];
+  int piv[64];
+};
+
+// Least squares min ||A x - b|| by Householder QR without pivoting; b is column nc of S.A.  A column whose
+// remaining part is (numerically) zero is dependent on earlier ones: its unknown is set to zero, which picks
+// one of the system's solutions (any solution locates the same nodes, Lemma l9 case (ii)).
+__device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
+  if (lane <= nc) {
+    double sq = 0.0;
+    for (int i = 0; i < nr; ++i) sq = fma(S.A[i][lane], S.A[i][lane], sq);
+    S.cn[lane] = sqrt(sq);
+  }
+  __syncthreads();
+  int row = 0;
+  for (int k = 0; k < nc; ++k) {  // every lane follows the same control flow (all conditions are wave-uniform)
+    bool dependent = row >= nr;
+    double akk = 0.0, tail = 0.0, nrm = 0.0;
+    if (!dependent) {
+      for (int i = row + 1; i < nr; ++i) tail = fma(S.A[i][k], S.A[i][k], tail);
+      akk = S.A[row][k];
+      nrm = sqrt(fma(akk, akk, tail));
+      dependent = !(nrm > SOLON_RANK_TOL * S.cn[k]);
+    }
+    if (dependent) {
+      if (lane == 0) S.piv[k] = -1;
+      continue;
+    }
+    const double alpha = akk >= 0.0 ? -nrm : nrm;
+    const double v0 = akk - alpha;
+    const double vtv = fma(v0, v0, tail);
+    if (lane > k && lane <= nc) {
+      double dot = v0 * S.A[row][lane];
+      for (int i = row + 1; i < nr; ++i) dot = fma(S.A[i][k], S.A[i][lane], dot);
+      const double cf = 2.0 * dot / vtv;
+      S.A[row][lane] -= cf * v0;
+      for (int i = row + 1; i < nr; ++i) S.A[i][lane] = fma(-cf, S.A[i][k], S.A[i][lane]);
+    }
+    __syncthreads();
+    if (lane == 0) {
+      S.A[row][k] = alpha;
+      S.piv[k] = row;
+    }
+    __syncthreads();
+    ++row;
+  }
+  if (lane == 0) {
+    for (int k = nc - 1; k >= 0; --k) {
+      const int r = S.piv[k];
+      if (r < 0) {
+        S.x[k] = 0.0;
+        continue;
+      }
+      double acc = S.A[r][nc];
+      for (int j = k + 1; j < nc; ++j) acc = fma(-S.A[r][j], S.x[j], acc);
+      S.x[k] = acc / S.A[r][k];
+    }
+  }
+  __syncthreads();
+}
+
+// Number of lanes (among `active`) whose value precedes this lane's in the total order (value, lane).
+__device__ int wave_rank(solve_smem& S, double v, bool active, int lane) {
+  S.val[lane] = v;
+  const unsigned long long mask = __ballot(active);
+  __syncthreads();
+  int rank = 0;
+  for (int j = 0; j < 64; ++j) {
+    if ((mask >> j) & 1ull) {
+      const double o = S.val[j];
+      rank += (o < v || (o == v && j < lane)) ? 1 : 0;
+    }
+  }
+  __syncthreads();
+  return rank;
+}
+
+struct solve_args {
+  int s, m, run_locator;
+  const int32_t* grp_off;
+  const int32_t* grp_nodes;
+  const float* w;
+  const double* rho;
+  int32_t* vmask;
+  int32_t* status;
+  int32_t* dec_rows;
+  float* dec_coef;
+};
+
+__global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
+  __shared__ solve_smem S;
+  const int g = blockIdx.x, lane = threadIdx.x;
+  const int n0 = a.grp_off[g], n = a.grp_off[g + 1] - n0;
+  const int m = a.m, s = a.s;
+  const bool in_group = lane < n;
+  const int node = in_group ? a.grp_nodes[n0 + lane] : -1;
+  const double wi = in_group ? (double)a.w[node] : 0.0;
+  int st = SOLON_OK;
+  bool located = false;
+
+  if (a.run_locator) {
+    const double rho = in_group ? a.rho[node] : 0.0;
+    const bool finite = in_group && isfinite(rho);
+    const unsigned long long fin_mask = __ballot(finite);
+    const int nfin = __popcll(fin_mask);
+    const int nnonfin = n - nfin;
+    located = in_group && !finite;  // a non-finite projection names its sender at once
+    if (nnonfin > s) {
+      st = SOLON_E_DECODE;
+    } else if (nfin > 0) {
+      // scale: median |rho| over the finite entries (honest nodes are a strict majority); max if that is zero
+      const double ar = fabs(rho);
+      const int rk = wave_rank(S, ar, finite, lane);
+      if (finite && rk == (nfin - 1) / 2) S.med[0] = ar;
+      if (finite && rk == nfin / 2) S.med[1] = ar;
+      __syncthreads();
+      double scale = 0.5 * (S.med[0] + S.med[1]);
+      if (scale == 0.0) {
+        const int top = nfin - 1;
+        __syncthreads();
+        if (finite && rk == top) S.med[0] = ar;
+        __syncthreads();
+        scale = S.med[0];
+      }
+      __syncthreads();
+      if (scale > 0.0) {
+        // compact the finite points: position = number of finite lanes below this one
+        const int pos = __popcll(fin_mask & ((1ull << lane) - 1ull));
+        const double yi = finite ? rho / scale : 0.0;
+        if (finite) {
+          S.y[pos] = yi;
+          S.wv[pos] = wi;
+        }
+        __syncthreads();
+        const int se = s - nnonfin;  // locator degree left for the finite points
+        const bool pt = lane < nfin;
+        const double yl = pt ? S.y[lane] : 0.0, wl = pt ? S.wv[lane] : 0.0;
+        bool cand = false;
+        if (se > 0) {
+          const int nn = m + se;      // numerator unknowns (Chebyshev coefficients 0 .. m+se-1)
+          const int nc = nn + se;     // + locator unknowns (coefficients 0 .. se-1; T_se has coefficient one)
+          if (pt) {
+            const double eq = 1.0 / fmax(1.0, fabs(yl));
+            double t0 = 1.0, t1 = wl;
+            for (int k = 0; k < nn; ++k) {  // se < nn
+              if (k < nn) S.A[lane][k] = t0 * eq;
+              if (k < se) S.A[lane][nn + k] = -yl * t0 * eq;
+              if (k == se) S.A[lane][nc] = yl * t0 * eq;
+              const double t2 = 2.0 * wl * t1 - t0;
+              t0 = t1;
+              t1 = t2;
+            }
+          }
+          __syncthreads();
+          wave_least_squares(S, nfin, nc, lane);
+          // |D(w_i)|: every corrupted point is a root of every solution's locator polynomial
+          double dv = 0.0;
+          if (pt) {
+            double t0 = 1.0, t1 = wl;
+            for (int k = 0; k <= se; ++k) {
+              dv = fma(k < se ? S.x[nn + k] : 1.0, t0, dv);
+              const double t2 = 2.0 * wl * t1 - t0;
+              t0 = t1;
+              t1 = t2;
+            }
+            dv = fabs(dv);
+          }
+          const int drank = wave_rank(S, dv, pt, lane);
+          cand = pt && drank < se;
+        }
+        // P_j: least-squares polynomial of degree m-1 through the points that are not candidates
+        if (pt) {
+          double t0 = 1.0, t1 = wl;
+          for (int k = 0; k < m; ++k) {
+            S.A[lane][k] = cand ? 0.0 : t0;
+            const double t2 = 2.0 * wl * t1 - t0;
+            t0 = t1;
+            t1 = t2;
+          }
+          S.A[lane][m] = cand ? 0.0 : yl;
+        }
+        __syncthreads();
+        wave_least_squares(S, nfin, m, lane);
+        bool flag = false;
+        if (pt) {
+          double pv = 0.0, t0 = 1.0, t1 = wl;
+          for (int k = 0; k < m; ++k) {
+            pv = fma(S.x[k], t0, pv);
+            const double t2 = 2.0 * wl * t1 - t0;
+            t0 = t1;
+            t1 = t2;
+          }
+          flag = !(fabs(pv - yl) <= SOLON_TAU);
+        }
+        const unsigned long long flag_mask = __ballot(flag);  // indexed by compacted position
+        if (__popcll(flag_mask) > se) st = SOLON_E_DECODE;
+        if (finite && ((flag_mask >> pos) & 1ull)) located = true;
+      }
+    }
+    if (in_group) a.vmask[node] = located ? 1 : 0;
+  } else {
+    located = in_group && a.vmask[node] != 0;
+  }
+
+  // ---- psi set-up: m honest nodes in Leja order (each next point maximises the product of distances to the
+  // ones already taken), which keeps the m x m Vandermonde well conditioned; then its inverse, column t of
+  // which holds the monomial coefficients of the Lagrange basis polynomial of the t-th chosen point.
+  const bool honest = in_group && !located;
+  const int nh = __popcll(__ballot(honest));
+  if (st == SOLON_OK && nh < m) st = SOLON_E_DECODE;
+  if (st == SOLON_OK) {
+    bool taken = false;
+    double prod = fabs(wi);  // first pick: largest |w|
+    for (int t = 0; t < m; ++t) {
+      const bool avail = honest && !taken;
+      const int rk = wave_rank(S, avail ? -prod : 0.0, avail, lane);  // rank 0 = largest product, lowest lane on ties
+      if (avail && rk == 0) {
+        S.med[0] = wi;
+        taken = true;
+      }
+      __syncthreads();
+      const double wsel = S.med[0];
+      __syncthreads();
+      const double dist = fabs(wi - wsel);
+      prod = (t == 0) ? dist : prod * dist;
+    }
+    const unsigned long long taken_mask = __ballot(taken);
+    const int tpos = __popcll(taken_mask & ((1ull << lane) - 1ull));  // ascending node order
+    if (taken) {
+      S.val[tpos] = wi;
+      a.dec_rows[g * m + tpos] = node;
+    }
+    __syncthreads();
+    if (taken) {
+      double* poly = S.lag[tpos];
+      poly[0] = 1.0;
+      int deg = 0;
+      double den = 1.0;
+      for (int u = 0; u < m; ++u) {
+        if (u == tpos) continue;
+        const double wu = S.val[u];
+        poly[deg + 1] = 0.0;
+        for (int l = deg + 1; l >= 1; --l) poly[l] = poly[l - 1] - wu * poly[l];  // multiply by (w - w_u)
+        poly[0] = -wu * poly[0];
+        ++deg;
+        den *= (wi - wu);
+      }
+      for (int l = 0; l < m; ++l) poly[l] /= den;
+    }
+    __syncthreads();
+    double rowsum = 0.0;
+    if (lane < m) {
+      for (int t = 0; t < m; ++t) {
+        const double c = S.lag[t][lane];
+        rowsum += fabs(c);
+        a.dec_coef[(g * m + lane) * m + t] = (float)c;  // T[g][l][t]
+      }
+    }
+    const unsigned long long bad = __ballot(lane < m && !(rowsum <= SOLON_INV_NORM_MAX));
+    if (bad) st = SOLON_E_NUMERIC;
+  }
+  if (lane == 0) a.status[g] = st;
+}
+
+int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st) {
+  solve_args a;
+  a.s = plan->s; a.m = plan->m; a.run_locator = run_locator ? 1 : 0;
+  a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
+  a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
+  hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
+  SOLON_HIP(hipGetLastError());
+  return SOLON_OK;
+}
+
+static int collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host /*P or null*/, double* rho_host /*P or null*/) {
+  // staging layout: [double rho[P]] [int32 vmask[P]] [int32 status[q]]
+  char* base = (char*)plan->pinned;
+  double* h_rho = (double*)base;
+  int32_t* h_vmask = (int32_t*)(base + sizeof(double) * plan->P);
+  int32_t* h_status = h_vmask + plan->P;
+  if (rho_host) SOLON_HIP(hipMemcpyAsync(h_rho, plan->dev.rho, sizeof(double) * plan->P, hipMemcpyDeviceToHost, st));
+  if (vmask_host) SOLON_HIP(hipMemcpyAsync(h_vmask, plan->dev.vmask, sizeof(int32_t) * plan->P, hipMemcpyDeviceToHost, st));
+  SOLON_HIP(hipMemcpyAsync(h_status, plan->dev.status, sizeof(int32_t) * plan->q, hipMemcpyDeviceToHost, st));
+  SOLON_HIP(hipStreamSynchronize(st));
+  if (rho_host) std::copy(h_rho, h_rho + plan->P, rho_host);
+  if (vmask_host) std::copy(h_vmask, h_vmask + plan->P, vmask_host);
+  int worst = SOLON_OK;
+  for (int g = 0; g < plan->q; ++g) {
+    if (h_status[g] != SOLON_OK && worst == SOLON_OK) {
+      worst = h_status[g];
+      if (worst == SOLON_E_DECODE) solon_set_error("group %d cannot be explained by <= s = %d corrupted nodes", g, plan->s);
+      else solon_set_error("group %d: the m x m Vandermonde of the chosen honest nodes is too ill-conditioned", g);
+    }
+  }
+  return worst;
+}
+
+extern "C" int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const float* f, int32_t* byz_idx, int32_t* n_byz,
+                            double* rho_out, void* hip_stream) {
+  if (!plan || !R || !f) {
+    solon_set_error("solon_locate: null argument");
+    return SOLON_E_INVAL;
+  }
+  if (ldr < plan->d_c) {
+    solon_set_error("solon_locate: ldr %lld < d_c %lld", (long long)ldr, (long long)plan->d_c);
+    return SOLON_E_INVAL;
+  }
+  if (!plan->ws) {
+    solon_set_error("solon_locate: the plan has no device workspace (no GPU at creation)");
+    return SOLON_E_HIP;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  int rc = solon_launch_project(plan, R, ldr, f, st);
+  if (rc != SOLON_OK) return rc;
+  rc = solon_launch_solve(plan, true, st);
+  if (rc != SOLON_OK) return rc;
+  if (!byz_idx && !n_byz && !rho_out) return SOLON_OK;
+  std::vector<int32_t> vm(plan->P);
+  rc = collect_status(plan, st, vm.data(), rho_out);
+  if (rc == SOLON_E_HIP) return rc;
+  int cnt = 0;
+  for (int j = 0; j < plan->P; ++j) {
+    if (plan->group_of_node[j] >= 0 && vm[j]) {
+      if (byz_idx && cnt < plan->q * plan->s) byz_idx[cnt] = j;
+      ++cnt;
+    }
+  }
+  if (n_byz) *n_byz = cnt;
+  return rc;
+}
+
+extern "C" int solon_decode_status(solon_plan* plan, void* hip_stream) {
+  if (!plan) {
+    solon_set_error("solon_decode_status: null plan");
+    return SOLON_E_INVAL;
+  }
+  if (!plan->ws) {
+    solon_set_error("solon_decode_status: the plan has no device workspace");
+    return SOLON_E_HIP;
+  }
+  return collect_status(plan, (hipStream_t)hip_stream, nullptr, nullptr);
+}

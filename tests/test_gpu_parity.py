@@ -1,0 +1,212 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Bars: located set bit-exact; rho to 1e-12 relative; encode rel-L2 <= 1e-6;
+decoded aggregate rel-L2 <= 1e-4 (against the oracle's decode of the same R and against the plain sum)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2110_01595_amd as solon
+import workloads
+from oracle import solon_oracle as so
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda:0")
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def host(t):
+    return t.float().cpu().numpy()
+
+
+def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, seed=0, dist="normal", sigma=0.01,
+             check_bruteforce=False, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False):
+    """One encode -> attack -> locate -> decode round, compared step by step with the oracle."""
+    say("case", dict(P=P, s=s, m=m, d=d, dtype=dtype, attack=attack, byz=byz, seed=seed, pad=pad))
+    cfg = dict(P=(P if B is None else B), d=d, dtype=dtype, dist=dist, sigma=sigma, mu_sigma=0.03)
+    plan = solon.Plan(P, s, m, d, B=B, dtype=solon.SOLON_BF16 if dtype == "bf16" else solon.SOLON_F32,
+                      group_of_node=group_of_node, group_of_batch=group_of_batch, w=w)
+    oplan = so.make_plan(P, s, m, B=B, group_of_node=group_of_node, group_of_batch=group_of_batch, w=w)
+    d_c = plan.d_c
+    assert d_c == so.message_length(d, m)
+    G = workloads.make_gradients(cfg, DEV, 100 + seed, d=d)
+    if pad:  # rows that are not 16-byte aligned: exercises the general kernels
+        Gp = torch.zeros((G.shape[0], d + pad), dtype=G.dtype, device=DEV)
+        Gp[:, :d] = G
+        G = Gp[:, :d]
+    Zfull = torch.full((P, d_c + pad), 7.0, dtype=torch.float32, device=DEV)
+    Z = Zfull[:, :d_c]
+    solon.solon_encode(plan, G, Z)
+    torch.cuda.synchronize()
+    if pad:
+        assert bool((Zfull[:, d_c:] == 7.0).all())                      # nothing written past a row's end
+    Gh = host(G)
+    Z_ref = so.encode(oplan, Gh)
+    active = np.concatenate(oplan.nodes)
+    Zh = host(Z)
+    zmax = np.abs(Z_ref).max() + 1e-30
+    assert np.abs(Zh[active] - Z_ref[active]).max() <= 4e-6 * zmax
+    assert so.rel_l2(Zh[active], Z_ref[active]) <= 1e-6
+
+    if byz is None:
+        byz = workloads.pick_byzantine(P, s if n_byz is None else n_byz, 200 + seed, within=active.tolist())
+    R = Zfull.clone()[:, :d_c] if pad else Z.clone()
+    workloads.apply_attack(R, byz, attack, 300 + seed)
+    f = workloads.make_projection(d_c, DEV, 400 + seed)
+    V, rho = solon.solon_locate(plan, R, f, want_rho=True)
+    Rh, fh = R.cpu().numpy(), f.cpu().numpy()
+    rho_ref = so.project(Rh, fh)
+    fin = np.isfinite(rho_ref)
+    assert np.array_equal(fin[active], np.isfinite(rho)[active])
+    scale = np.abs(rho_ref[fin]).max() + 1e-300
+    assert np.abs(rho[fin] - rho_ref[fin]).max() <= 1e-12 * max(scale, (np.abs(Rh[fin]).astype(np.float64) @ np.abs(fh)).max())
+    V_ref = so.locate(oplan, rho_ref, "bw")
+    assert V == V_ref, (V, V_ref)
+    assert V == sorted(byz), (V, byz)
+    if check_bruteforce:
+        assert so.locate(oplan, rho_ref, "bruteforce") == V
+
+    u = torch.full((d + 3,), 5.0, dtype=torch.float32, device=DEV)
+    solon.solon_decode(plan, R, u[:d], byz=V if decode_from_host else None)
+    assert solon.solon_decode_status(plan) == solon.SOLON_OK
+    torch.cuda.synchronize()
+    assert bool((u[d:] == 5.0).all())
+    uh = u[:d].cpu().numpy()
+    u_ref = so.decode(oplan, Rh, V_ref, d)
+    assert so.rel_l2(uh, u_ref) <= 1e-4
+    assert so.rel_l2(uh, so.plain_sum(Gh)) <= 1e-4
+    return plan
+
+
+# ------------------------------------------------------------------ small cases: several tiles + ragged tail
+SMALL = [
+    # P, s, m, d
+    (7, 1, 1, 4096), (7, 1, 1, 70_001), (15, 1, 2, 40_002), (15, 1, 2, 131_073), (31, 2, 2, 50_000),
+    (63, 3, 4, 40_004), (63, 3, 4, 65_539), (100, 5, 4, 33_001), (9, 1, 3, 30_001), (20, 2, 5, 25_003),
+    (100, 5, 10, 50_010), (24, 2, 8, 64_001), (4, 1, 2, 2), (4, 1, 2, 1), (10, 3, 4, 3), (64, 0, 16, 70_000),
+]
+
+
+@pytest.mark.parametrize("P,s,m,d", SMALL)
+def test_round_fp32(P, s, m, d):
+    run_case(P, s, m, d, attack="flip10", seed=P + m, check_bruteforce=(P <= 15))
+
+
+@pytest.mark.parametrize("P,s,m,d", [(7, 1, 1, 20_001), (15, 1, 2, 40_002), (100, 5, 4, 33_001), (63, 3, 4, 40_008), (20, 2, 5, 25_003)])
+def test_round_bf16(P, s, m, d):
+    run_case(P, s, m, d, dtype="bf16", attack="mix", dist="student3", sigma=1e-3, seed=7)
+
+
+@pytest.mark.parametrize("attack", ["flip10", "noise100", "alie", "collude50", "mix", "paper", "nan", "inf", "huge"])
+@pytest.mark.parametrize("P,s,m", [(15, 1, 2), (31, 2, 2), (63, 3, 4), (100, 5, 4)])
+def test_attacks(P, s, m, attack):
+    dist = "shared_mean" if attack == "alie" else "normal"
+    run_case(P, s, m, 24_000, attack=attack, dist=dist, seed=3)
+
+
+@pytest.mark.parametrize("P,s,m", [(31, 2, 2), (63, 3, 4), (100, 5, 4)])
+def test_all_adversaries_in_one_group_and_fewer_than_s(P, s, m):
+    oplan = so.make_plan(P, s, m)
+    run_case(P, s, m, 16_384, attack="mix", byz=oplan.nodes[0][:s].tolist(), seed=1)
+    run_case(P, s, m, 16_384, attack="mix", byz=oplan.nodes[oplan.q - 1][-s:].tolist(), seed=2)
+    run_case(P, s, m, 16_384, attack="noise100", n_byz=s - 1, seed=3)
+    run_case(P, s, m, 16_384, attack="noise100", n_byz=0, seed=4)
+
+
+def test_unaligned_rows_use_general_kernels():
+    run_case(15, 1, 2, 40_002, pad=1, seed=5)
+    run_case(63, 3, 4, 10_001, pad=3, seed=6)
+    run_case(100, 5, 4, 9_999, pad=2, dtype="bf16", seed=7)
+
+
+def test_decode_with_host_supplied_set():
+    run_case(31, 2, 2, 20_000, attack="noise100", decode_from_host=True, seed=8)
+
+
+def test_custom_tables_idle_nodes_and_points():
+    gon = [0, 0, 0, 0, 1, 1, 1, 1, -1, 1]
+    w = [0.9, -0.4, 0.3, -0.8, 1.5, -1.25, 0.5, 2.0, 1.0, -0.75]
+    run_case(10, 1, 2, 12_346, B=6, group_of_node=gon, group_of_batch=[0, 1, 0, 1, 0, 1], w=w, byz=[2, 9], attack="flip10", seed=9)
+
+
+def test_colluding_valid_codeword_of_fake_gradient():
+    P, s, m, d = 14, 5, 4, 8192
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    G, Gfake = workloads.make_gradients(cfg, DEV, 1, d=d), workloads.make_gradients(cfg, DEV, 2, d=d)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    Zf = torch.empty_like(Z)
+    solon.solon_encode(plan, G, Z)
+    solon.solon_encode(plan, Gfake, Zf)
+    bad = [1, 4, 6, 9, 13]
+    R = Z.clone()
+    R[bad] = Zf[bad]
+    f = workloads.make_projection(plan.d_c, DEV, 3)
+    V, _ = solon.solon_locate(plan, R, f)
+    assert V == bad == so.locate(oplan, so.project(R.cpu().numpy(), f.cpu().numpy()))
+    u = torch.empty(d, dtype=torch.float32, device=DEV)
+    solon.solon_decode(plan, R, u)
+    assert so.rel_l2(u.cpu().numpy(), so.plain_sum(host(G))) <= 1e-4
+
+
+def test_more_than_s_corruptions_is_reported_not_decoded():
+    P, s, m, d = 15, 1, 2, 4096
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    G = workloads.make_gradients(cfg, DEV, 1, d=d)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    R = workloads.apply_attack(Z.clone(), [0, 2], "noise100", 5)       # two in group 0, s = 1
+    f = workloads.make_projection(plan.d_c, DEV, 3)
+    with pytest.raises(so.OracleError):
+        so.locate(oplan, so.project(R.cpu().numpy(), f.cpu().numpy()))
+    with pytest.raises(solon.SolonError) as e:
+        solon.solon_locate(plan, R, f)
+    assert e.value.code == solon.SOLON_E_DECODE
+    solon.solon_locate(plan, R, f, want_host=False)                      # asynchronous form reports through the status call
+    assert solon.solon_decode_status(plan) == solon.SOLON_E_DECODE
+    with pytest.raises(solon.SolonError) as e:                           # a host-supplied set that leaves < m nodes in a group
+        solon.solon_decode(plan, R, torch.empty(d, device=DEV), byz=[0, 1, 2, 3])
+    assert e.value.code == solon.SOLON_E_DECODE
+
+
+def test_all_zero_gradients():
+    P, s, m, d = 15, 1, 2, 4096
+    plan = solon.Plan(P, s, m, d)
+    G = torch.zeros((P, d), device=DEV)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    f = workloads.make_projection(plan.d_c, DEV, 3)
+    V, _ = solon.solon_locate(plan, Z, f)
+    assert V == [] == so.locate(so.make_plan(P, s, m), np.zeros(P))
+    u = torch.ones(d, device=DEV)
+    solon.solon_decode(plan, Z, u)
+    assert float(u.abs().max()) == 0.0
+
+
+def test_projection_is_bit_reproducible():
+    P, s, m, d = 63, 3, 4, 400_000
+    plan = solon.Plan(P, s, m, d)
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    G = workloads.make_gradients(cfg, DEV, 1, d=d)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    f = workloads.make_projection(plan.d_c, DEV, 3)
+    rhos = [solon.solon_locate(plan, Z, f, want_rho=True)[1] for _ in range(3)]
+    assert np.array_equal(rhos[0], rhos[1]) and np.array_equal(rhos[0], rhos[2])
+
+
+def test_linearity_of_encode_and_decode():
+    P, s, m, d = 31, 2, 2, 30_000
+    plan = solon.Plan(P, s, m, d)
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    G1, G2 = workloads.make_gradients(cfg, DEV, 1, d=d), workloads.make_gradients(cfg, DEV, 2, d=d)
+    Z1, Z2, Z3 = (torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV) for _ in range(3))
+    solon.solon_encode(plan, G1, Z1)
+    solon.solon_encode(plan, G2, Z2)
+    solon.solon_encode(plan, G1 * 0.5 - 2.0 * G2, Z3)
+    assert so.rel_l2(Z3.cpu().numpy(), (0.5 * Z1 - 2.0 * Z2).cpu().numpy()) <= 1e-6
