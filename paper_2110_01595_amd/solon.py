@@ -38,6 +38,9 @@ def lib():
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libsolon.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # torch ships its own HIP runtime; load it first so that libsolon.so binds to that same runtime
+    # (two HIP runtimes in one process do not see the device).
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
     L.solon_plan_create.argtypes = [ctypes.POINTER(vp), i32, i32, i32, i32, i64, i32, vp, vp, vp]
