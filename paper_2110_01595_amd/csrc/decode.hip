@@ -69,7 +69,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
   constexpr int CH = (M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4);  // CH * M is a multiple of four
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)u % 16 == 0);
   const int64_t nunits = (plan->d_c + CH - 1) / CH;
-  const int cap = solon_tuning("decode_blocks", 16384);
+  const int cap = solon_tuning("decode_blocks", 1 << 22);
   int64_t blocks = std::min<int64_t>((nunits + 255) / 256, cap);
   blocks = std::max<int64_t>(blocks, 1);
   if (vec)

@@ -145,7 +145,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
   constexpr int UE = lcm_c(M, LV);
   const int threads = 256;
   const int q = plan->q;
-  const int cap = solon_tuning("encode_blocks", 8192);  // total blocks of the grid-stride launch
+  const int cap = solon_tuning("encode_blocks", 1 << 22);  // total blocks of the grid-stride launch
   const bool nt = solon_tuning("encode_nt", 1) != 0;
   const int mult = (M == 1 || M == 2 || M == 4) ? solon_tuning("encode_unit_mult", 1) : 1;
   int64_t done_chunks = 0;

@@ -92,7 +92,7 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
   const int rows_per_bunch = (P + nbunch - 1) / nbunch;
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
   const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
-  const int cap = solon_tuning("project_blocks", 4096);
+  const int cap = solon_tuning("project_blocks", 8192);
   int64_t ntiles = std::max<int64_t>(1, (work + 255) / 256);
   ntiles = std::min<int64_t>(ntiles, std::max(1, cap / nbunch));
   ntiles = std::min<int64_t>(ntiles, SOLON_PROJ_MAX_TILES);
