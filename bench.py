@@ -137,12 +137,25 @@ def main():
     ap.add_argument("--config", default="C5")
     ap.add_argument("--also", default="C4", help="comma-separated further workloads reported inside the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="first run one plain device copy of 4 GiB (reads 4 GiB, writes 4 GiB): the dispatch whose rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the path has no collectives and every box has one GPU (--gpus %d refused)" % args.gpus)
 
     import paper_2110_01595_amd as solon
     solon.lib()                                              # fail loudly if the HIP library is missing
+
+    if args.calibrate_copy:
+        import torch
+        src = torch.ones(1 << 30, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                                       # elementwise copy kernel, 2^32 bytes each way
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
     others = []
