@@ -17,10 +17,10 @@ template <> struct chunk_vec<4> { typedef f32x4 type; };
 template <int M, int CH, bool VEC>
 __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ rows,
                                                          const float* __restrict__ coef, float* __restrict__ u, int64_t d,
-                                                         int64_t d_c) {
+                                                         int64_t d_c, int64_t p_begin) {
   const int64_t nunits = (d_c + CH - 1) / CH;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; unit < nunits; unit += stride) {
+  for (int64_t unit = p_begin / CH + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; unit < nunits; unit += stride) {
     const int64_t p = unit * CH;
     const bool full = (p + CH <= d_c) && ((p + CH) * M <= d);
     float out[CH * M];
@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict_
         }
 #pragma unroll
         for (int l = 0; l < M; ++l) {
-          const float cf = coef[(g * M + l) * M + t];
+          const float cf = coef[(g * M + t) * M + l];
 #pragma unroll
           for (int c = 0; c < CH; ++c) out[c * M + l] = fmaf(cf, v[c], out[c * M + l]);
         }
@@ -64,20 +64,61 @@ __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict_
   }
 }
 
+// Tiled path for compression ratios other than 1, 2, 4.  A block owns 256 consecutive chunks: each thread
+// recombines its chunk from coalesced 4-byte loads, the 256 m results pass through LDS and leave as coalesced
+// 16-byte stores.
+template <int M>
+__global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __restrict__ R, int64_t ldr, int q,
+                                                              const int32_t* __restrict__ rows, const float* __restrict__ coef,
+                                                              float* __restrict__ u) {
+  __shared__ float tile_out[256 * M];
+  const int tid = threadIdx.x;
+  const int64_t tile = blockIdx.x;
+  const int64_t p = tile * 256 + tid;
+  float out[M];
+#pragma unroll
+  for (int l = 0; l < M; ++l) out[l] = 0.0f;
+  for (int g = 0; g < q; ++g) {
+#pragma unroll
+    for (int t = 0; t < M; ++t) {
+      const float v = __builtin_nontemporal_load(R + (int64_t)rows[g * M + t] * ldr + p);
+#pragma unroll
+      for (int l = 0; l < M; ++l) out[l] = fmaf(coef[(g * M + t) * M + l], v, out[l]);
+    }
+  }
+#pragma unroll
+  for (int l = 0; l < M; ++l) tile_out[tid * M + l] = out[l];
+  __syncthreads();
+  float* dst = u + tile * (256 * M);
+  for (int v = tid; v < 64 * M; v += 256)
+    __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(&tile_out[4 * v]), reinterpret_cast<f32x4*>(dst + 4 * v));
+}
+
 template <int M>
 static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
   constexpr int CH = (M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4);  // CH * M is a multiple of four
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)u % 16 == 0);
-  const int64_t nunits = (plan->d_c + CH - 1) / CH;
   const int cap = solon_tuning("decode_blocks", 1 << 22);
+  int64_t p_begin = 0;
+  if constexpr (M != 1 && M != 2 && M != 4) {
+    const int64_t ntiles = plan->d / (256 * M);  // tiles that lie entirely below d
+    if (ntiles > 0 && (uintptr_t)u % 16 == 0 && solon_tuning("decode_force_generic", 0) == 0) {
+      hipLaunchKernelGGL((recombine_tile_kernel<M>), dim3((unsigned)ntiles), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                         plan->dev.dec_coef, u);
+      SOLON_HIP(hipGetLastError());
+      p_begin = ntiles * 256;
+    }
+  }
+  if (p_begin >= plan->d_c) return SOLON_OK;
+  const int64_t nunits = (plan->d_c - p_begin + CH - 1) / CH;
   int64_t blocks = std::min<int64_t>((nunits + 255) / 256, cap);
   blocks = std::max<int64_t>(blocks, 1);
   if (vec)
     hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin);
   else
     hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }

@@ -136,47 +136,92 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
   }
 }
 
-static constexpr int gcd_c(int a, int b) { return b == 0 ? a : gcd_c(b, a % b); }
-static constexpr int lcm_c(int a, int b) { return a / gcd_c(a, b) * b; }
+// Tiled path for compression ratios that do not divide the 16-byte load width.  A block owns 256 consecutive
+// chunks of one group (256 m coordinates): the group sum is accumulated position-wise with coalesced 16-byte
+// loads (that part does not depend on m), parked in LDS, and then each thread picks up the m coefficients of its
+// own chunk and writes one message element per node (coalesced 4-byte stores).
+template <int M, typename T, bool NT>
+__global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
+  constexpr int LV = load_traits<T>::LV;
+  constexpr int NVEC = 256 * M / LV;          // 16-byte vectors per row and tile
+  constexpr int NI = (NVEC + 255) / 256;      // vectors per thread
+  __shared__ float ybar[256 * M];
+  const int g = blockIdx.y, tid = threadIdx.x;
+  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int64_t tile = blockIdx.x;
+  const T* base = static_cast<const T*>(a.G) + tile * (256 * M);
+  float acc[NI][LV];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
+#pragma unroll 2
+  for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+    const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int v = tid + 256 * i;
+      if (NVEC % 256 == 0 || v < NVEC) load_add<NT>(src + v * LV, acc[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int v = tid + 256 * i;
+    if (NVEC % 256 == 0 || v < NVEC) {
+#pragma unroll
+      for (int e = 0; e < LV; e += 4)
+        *reinterpret_cast<f32x4*>(&ybar[v * LV + e]) = (f32x4){acc[i][e], acc[i][e + 1], acc[i][e + 2], acc[i][e + 3]};
+    }
+  }
+  __syncthreads();
+  float y[M];
+#pragma unroll
+  for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
+  float* zbase = a.Z + tile * 256 + tid;
+  for (int t = n0; t < n1; ++t) {
+    const int j = a.grp_nodes[t];
+    const float wj = a.w[j];
+    float h = y[M - 1];
+#pragma unroll
+    for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
+    if (NT) __builtin_nontemporal_store(h, zbase + (int64_t)j * a.ldz); else zbase[(int64_t)j * a.ldz] = h;
+  }
+}
 
 template <int M, typename T>
 static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool aligned, hipStream_t st) {
   constexpr int LV = load_traits<T>::LV;
-  constexpr int UE = lcm_c(M, LV);
   const int threads = 256;
   const int q = plan->q;
-  const int cap = solon_tuning("encode_blocks", 1 << 22);  // total blocks of the grid-stride launch
+  const int cap = solon_tuning("encode_blocks", 1 << 22);  // blocks per group; below the work size the kernel strides
   const bool nt = solon_tuning("encode_nt", 1) != 0;
-  const int mult = (M == 1 || M == 2 || M == 4) ? solon_tuning("encode_unit_mult", 1) : 1;
   int64_t done_chunks = 0;
   if (aligned && solon_tuning("encode_force_generic", 0) == 0) {
-    const int ue = UE * mult;
-    const int64_t nunits = plan->d / ue;
-    if (nunits > 0) {
-      int64_t bx = (nunits + threads - 1) / threads;
-      bx = std::min<int64_t>(bx, std::max(1, cap / q));
-      dim3 grid((unsigned)bx, (unsigned)q);
-#define SOLON_ENC_LAUNCH(UEV)                                                                               \
-  do {                                                                                                      \
-    if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, UEV, T, true>), grid, dim3(threads), 0, st, a, nunits); \
-    else hipLaunchKernelGGL((encode_vec_kernel<M, UEV, T, false>), grid, dim3(threads), 0, st, a, nunits);   \
-  } while (0)
-      if constexpr (M == 1 || M == 2 || M == 4) {
-        if (mult == 4) SOLON_ENC_LAUNCH(UE * 4);
-        else if (mult == 2) SOLON_ENC_LAUNCH(UE * 2);
-        else SOLON_ENC_LAUNCH(UE);
-      } else {
-        SOLON_ENC_LAUNCH(UE);
+    if constexpr (LV % M == 0) {  // m divides the load width: one 16-byte load per row and thread
+      const int64_t nunits = plan->d / LV;
+      if (nunits > 0) {
+        int64_t bx = std::min<int64_t>((nunits + threads - 1) / threads, std::max(1, cap));
+        dim3 grid((unsigned)bx, (unsigned)q);
+        if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, true>), grid, dim3(threads), 0, st, a, nunits);
+        else hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, false>), grid, dim3(threads), 0, st, a, nunits);
+        SOLON_HIP(hipGetLastError());
+        done_chunks = nunits * (LV / M);
       }
-#undef SOLON_ENC_LAUNCH
-      SOLON_HIP(hipGetLastError());
-      done_chunks = nunits * (ue / M);
+    } else {
+      const int64_t ntiles = plan->d / (256 * M);
+      if (ntiles > 0) {
+        dim3 grid((unsigned)ntiles, (unsigned)q);
+        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a);
+        else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a);
+        SOLON_HIP(hipGetLastError());
+        done_chunks = ntiles * 256;
+      }
     }
   }
   if (done_chunks < plan->d_c) {  // ragged tail, or the whole range when rows are not 16-byte aligned
     const int64_t n = plan->d_c - done_chunks;
-    int64_t bx = (n + threads - 1) / threads;
-    bx = std::min<int64_t>(bx, std::max(1, cap / q));
+    int64_t bx = std::min<int64_t>((n + threads - 1) / threads, std::max(1, cap));
     hipLaunchKernelGGL((encode_chunk_kernel<M, T>), dim3((unsigned)bx, (unsigned)q), dim3(threads), 0, st, a, done_chunks,
                        plan->d_c);
     SOLON_HIP(hipGetLastError());

@@ -183,20 +183,99 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
   __syncthreads();
 }
 
-// Number of lanes (among `active`) whose value precedes this lane's in the total order (value, lane).
-__device__ int wave_rank(solve_smem& S, double v, bool active, int lane) {
-  S.val[lane] = v;
+// Value of `v` in lane `src` (src must be wave-uniform): two scalar broadcasts, no LDS.
+__device__ __forceinline__ double lane_bcast(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+
+// Number of lanes (among `active`, all below `n`) whose value precedes this lane's in the total order (value, lane).
+__device__ int wave_rank(double v, bool active, int n, int lane) {
   const unsigned long long mask = __ballot(active);
-  __syncthreads();
   int rank = 0;
-  for (int j = 0; j < 64; ++j) {
-    if ((mask >> j) & 1ull) {
-      const double o = S.val[j];
-      rank += (o < v || (o == v && j < lane)) ? 1 : 0;
+  for (int j = 0; j < n; ++j) {
+    const double o = lane_bcast(v, j);
+    if ((mask >> j) & 1ull) rank += (o < v || (o == v && j < lane)) ? 1 : 0;
+  }
+  return rank;
+}
+
+// The same least-squares solve with the matrix in registers: lane j holds column j (rows 0..NMAX-1, zero past
+// nr), the pivot column is broadcast lane to all with scalar reads, so no LDS round trips or barriers are needed.
+// Serves groups of up to NMAX nodes; the result goes to S.x like wave_least_squares'.
+template <int NMAX>
+__device__ void reg_least_squares(solve_smem& S, int nr, int nc, int lane) {
+  double col[NMAX];
+  double sq = 0.0;
+#pragma unroll
+  for (int i = 0; i < NMAX; ++i) {
+    col[i] = (i < nr && lane <= nc) ? S.A[i][lane] : 0.0;
+    sq = fma(col[i], col[i], sq);
+  }
+  const double cn = sqrt(sq);
+  int row = 0, myrow = -1;
+  for (int k = 0; k < nc; ++k) {
+    double v[NMAX];
+    double tail = 0.0, akk = 0.0;
+#pragma unroll
+    for (int i = 0; i < NMAX; ++i) {
+      v[i] = lane_bcast(col[i], k);
+      if (i > row) tail = fma(v[i], v[i], tail);
+      if (i == row) akk = v[i];
     }
+    const double nrm = sqrt(fma(akk, akk, tail));
+    if (row >= nr || !(nrm > SOLON_RANK_TOL * lane_bcast(cn, k))) continue;  // dependent column: unknown stays zero
+    const double alpha = akk >= 0.0 ? -nrm : nrm;
+    const double v0 = akk - alpha;
+    const double vtv = fma(v0, v0, tail);
+    if (lane > k && lane <= nc) {
+      double dot = 0.0;
+#pragma unroll
+      for (int i = 0; i < NMAX; ++i) {
+        const double vi = (i == row) ? v0 : v[i];
+        if (i >= row) dot = fma(vi, col[i], dot);
+      }
+      const double cf = 2.0 * dot / vtv;
+#pragma unroll
+      for (int i = 0; i < NMAX; ++i) {
+        const double vi = (i == row) ? v0 : v[i];
+        if (i >= row) col[i] = fma(-cf, vi, col[i]);
+      }
+    }
+    if (lane == k) {
+#pragma unroll
+      for (int i = 0; i < NMAX; ++i)
+        if (i == row) col[i] = alpha;
+      myrow = row;
+    }
+    ++row;
+  }
+  // column-oriented back substitution: lane nc holds the transformed right-hand side
+  for (int k = nc - 1; k >= 0; --k) {
+    const int r = __builtin_amdgcn_readlane(myrow, k);
+    double xk = 0.0;
+    if (r >= 0) {
+      double sel = 0.0;
+#pragma unroll
+      for (int i = 0; i < NMAX; ++i)
+        if (i == r) sel = col[i];
+      xk = lane_bcast(sel, nc) / lane_bcast(sel, k);
+#pragma unroll
+      for (int i = 0; i < NMAX; ++i) {
+        const double rik = lane_bcast(col[i], k);  // R[i][k]
+        if (lane == nc && i < r) col[i] = fma(-xk, rik, col[i]);
+      }
+    }
+    if (lane == 0) S.x[k] = xk;
   }
   __syncthreads();
-  return rank;
+}
+
+template <int NMAX>
+__device__ __forceinline__ void solve_least_squares(solve_smem& S, int nr, int nc, int lane) {
+  if constexpr (NMAX > 0) reg_least_squares<NMAX>(S, nr, nc, lane);
+  else wave_least_squares(S, nr, nc, lane);
 }
 
 struct solve_args {
@@ -211,6 +290,7 @@ struct solve_args {
   float* dec_coef;
 };
 
+template <int NMAX>
 __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   __shared__ solve_smem S;
   const int g = blockIdx.x, lane = threadIdx.x;
@@ -234,7 +314,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
     } else if (nfin > 0) {
       // scale: median |rho| over the finite entries (honest nodes are a strict majority); max if that is zero
       const double ar = fabs(rho);
-      const int rk = wave_rank(S, ar, finite, lane);
+      const int rk = wave_rank(ar, finite, n, lane);
       if (finite && rk == (nfin - 1) / 2) S.med[0] = ar;
       if (finite && rk == nfin / 2) S.med[1] = ar;
       __syncthreads();
@@ -276,7 +356,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
             }
           }
           __syncthreads();
-          wave_least_squares(S, nfin, nc, lane);
+          solve_least_squares<NMAX>(S, nfin, nc, lane);
           // |D(w_i)|: every corrupted point is a root of every solution's locator polynomial
           double dv = 0.0;
           if (pt) {
@@ -289,7 +369,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
             }
             dv = fabs(dv);
           }
-          const int drank = wave_rank(S, dv, pt, lane);
+          const int drank = wave_rank(dv, pt, nfin, lane);
           cand = pt && drank < se;
         }
         // P_j: least-squares polynomial of degree m-1 through the points that are not candidates
@@ -304,7 +384,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
           S.A[lane][m] = cand ? 0.0 : yl;
         }
         __syncthreads();
-        wave_least_squares(S, nfin, m, lane);
+        solve_least_squares<NMAX>(S, nfin, m, lane);
         bool flag = false;
         if (pt) {
           double pv = 0.0, t0 = 1.0, t1 = wl;
@@ -337,7 +417,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
     double prod = fabs(wi);  // first pick: largest |w|
     for (int t = 0; t < m; ++t) {
       const bool avail = honest && !taken;
-      const int rk = wave_rank(S, avail ? -prod : 0.0, avail, lane);  // rank 0 = largest product, lowest lane on ties
+      const int rk = wave_rank(avail ? -prod : 0.0, avail, n, lane);  // rank 0 = largest product, lowest lane on ties
       if (avail && rk == 0) {
         S.med[0] = wi;
         taken = true;
@@ -377,7 +457,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
       for (int t = 0; t < m; ++t) {
         const double c = S.lag[t][lane];
         rowsum += fabs(c);
-        a.dec_coef[(g * m + lane) * m + t] = (float)c;  // T[g][l][t]
+        a.dec_coef[(g * m + t) * m + lane] = (float)c;  // T[g][l][t], stored with l fastest
       }
     }
     const unsigned long long bad = __ballot(lane < m && !(rowsum <= SOLON_INV_NORM_MAX));
@@ -391,7 +471,12 @@ int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st) {
   a.s = plan->s; a.m = plan->m; a.run_locator = run_locator ? 1 : 0;
   a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
   a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
-  hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
+  // columns in registers for groups of up to 16 nodes, the LDS-resident solve beyond (a 32-row register
+  // variant was measured slower than the LDS loops: its unrolled code is fetched cold by a single wavefront)
+  if (plan->max_group <= 16 && solon_tuning("solve_lds", 0) == 0)
+    hipLaunchKernelGGL(solve_kernel<16>, dim3(plan->q), dim3(64), 0, st, a);
+  else
+    hipLaunchKernelGGL(solve_kernel<0>, dim3(plan->q), dim3(64), 0, st, a);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }

@@ -24,7 +24,7 @@ struct solon_dev {
   int32_t* vmask;        // [P] 1 = located
   int32_t* status;       // [q] per-group status of the last locate / decode set-up
   int32_t* dec_rows;     // [q * m] rows of R chosen for psi
-  float* dec_coef;       // [q][m][m] T[g][l][t]
+  float* dec_coef;       // [q][m][m] psi's coefficients T[g][l][t], stored as [g][t][l]
 };
 
 struct solon_plan {

@@ -85,7 +85,7 @@ SMALL = [
     # P, s, m, d
     (7, 1, 1, 4096), (7, 1, 1, 70_001), (15, 1, 2, 40_002), (15, 1, 2, 131_073), (31, 2, 2, 50_000),
     (63, 3, 4, 40_004), (63, 3, 4, 65_539), (100, 5, 4, 33_001), (9, 1, 3, 30_001), (20, 2, 5, 25_003),
-    (100, 5, 10, 50_010), (24, 2, 8, 64_001), (4, 1, 2, 2), (4, 1, 2, 1), (10, 3, 4, 3),
+    (100, 5, 10, 50_010), (24, 2, 8, 64_001), (4, 1, 2, 2), (4, 1, 2, 1), (10, 3, 4, 3), (26, 1, 6, 40_003), (30, 2, 7, 30_007),
 ]
 
 
@@ -101,7 +101,8 @@ def test_largest_compiled_compression_ratio():
     run_case(40, 1, 12, 36_000, seed=81, u_tol=5e-3)
 
 
-@pytest.mark.parametrize("P,s,m,d", [(7, 1, 1, 20_001), (15, 1, 2, 40_002), (100, 5, 4, 33_001), (63, 3, 4, 40_008), (20, 2, 5, 25_003)])
+@pytest.mark.parametrize("P,s,m,d", [(7, 1, 1, 20_001), (15, 1, 2, 40_002), (100, 5, 4, 33_001), (63, 3, 4, 40_008), (20, 2, 5, 25_003),
+                                     (24, 2, 8, 64_008), (100, 5, 10, 50_010), (18, 1, 3, 20_000)])
 def test_round_bf16(P, s, m, d):
     run_case(P, s, m, d, dtype="bf16", attack="mix", dist="student3", sigma=1e-3, seed=7)
 
