@@ -32,7 +32,7 @@ def algorithmic_bytes(cfg, plan):
     return dict(encode=enc, locate=loc, decode=dec, total=enc + loc + dec)
 
 
-def run_config(name, steps, warmup, want_cpu_baseline):
+def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False):
     import numpy as np
     import torch
 
@@ -40,18 +40,23 @@ def run_config(name, steps, warmup, want_cpu_baseline):
     import workloads
 
     dev = torch.device("cuda:0")
-    cfg = workloads.CONFIGS[name]
-    sd = workloads.seeds(name)
+    if cfg is None:
+        cfg = workloads.CONFIGS[name]
+        sd = workloads.seeds(name)
+    else:
+        sd = dict(G=1, f=2, byz=3, attack=4)
     P, s, m, d = cfg["P"], cfg["s"], cfg["m"], cfg["d"]
     plan = solon.Plan(P, s, m, d, dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
     d_c = plan.d_c
     G = workloads.make_gradients(cfg, dev, sd["G"])
-    Z = torch.empty((P, d_c), dtype=torch.float32, device=dev)
+    ld = (d_c + 63) // 64 * 64                             # rows of Z and R start on 256-byte boundaries
+    Z = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
     u = torch.empty(d, dtype=torch.float32, device=dev)
     f = workloads.make_projection(d_c, dev, sd["f"])
     byz = workloads.pick_byzantine(P, s, sd["byz"])
     solon.solon_encode(plan, G, Z)
-    R = Z.clone()
+    R = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
+    R.copy_(Z)
     workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
     torch.cuda.synchronize()
 
@@ -93,6 +98,14 @@ def run_config(name, steps, warmup, want_cpu_baseline):
         phase_GBps=dict(encode=ab["encode"] / enc_ms / 1e6, locate=ab["locate"] / loc_ms / 1e6, decode=ab["decode"] / dec_ms / 1e6),
         algorithmic_bytes=ab,
     )
+    if check_sum:   # Def. 1 of the paper over every coordinate: u against the fp64 column sum of G (torch, on the device)
+        num = den = 0.0
+        for c0 in range(0, d, 1 << 22):
+            ref = G[:, c0:c0 + (1 << 22)].sum(dim=0, dtype=torch.float64)
+            diff = u[c0:c0 + (1 << 22)].double() - ref
+            num += float((diff * diff).sum())
+            den += float((ref * ref).sum())
+        res["rel_l2_u_vs_plain_sum"] = (num / den) ** 0.5
     cpu = None
     if want_cpu_baseline:
         cpu = cpu_baseline(cfg, plan, G, R, f, byz)
@@ -129,6 +142,23 @@ def cpu_baseline(cfg, plan, G, R, f, byz):
                        % (W, plan.d_c, P, t1 - t0, "matches" if ok else "MISMATCH"))
 
 
+# Shapes of the paper's own cost study (time-breakdown figures of Sec. 4 and of the appendix): P = 100 nodes,
+# s = 5 with r_c in {2, 4, 6, 8, 10}, and r_c = 10 with s in {1..5}, on the three model sizes of Table 1.
+PAPER_MODELS = {"ResNet18": 11_173_000, "VGG13": 9_923_000, "LSTM": 7_332_000}
+
+
+def sweep_paper_shapes(steps, warmup):
+    shapes = [(5, m) for m in (2, 4, 6, 8, 10)] + [(s, 10) for s in (1, 2, 3, 4)]
+    for model, d in PAPER_MODELS.items():
+        for s, m in shapes:
+            cfg = dict(P=100, s=s, m=m, d=d, dtype="f32", dist="normal", sigma=0.01, attack="paper")
+            name = "%s_P100_s%d_m%d" % (model, s, m)
+            r, _ = run_config(name, steps, warmup, False, cfg=cfg, check_sum=True)
+            keep = ("workload", "P", "s", "m", "d", "q", "r", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps",
+                    "located_ok", "rel_l2_u_vs_plain_sum")
+            print(json.dumps({k: r[k] for k in keep}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +167,10 @@ def main():
     ap.add_argument("--config", default="C5")
     ap.add_argument("--also", default="C4", help="comma-separated further workloads reported inside the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
+                    help="launch-shape knob passed to solon_tune before the run (measurement aid; may be repeated)")
+    ap.add_argument("--sweep", choices=["paper"], default=None,
+                    help="instead of the headline line, run the paper's cost-study shapes and print one JSON line per shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain device copy of 4 GiB (reads 4 GiB, writes 4 GiB): the dispatch whose rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels")
@@ -146,6 +180,9 @@ def main():
 
     import paper_2110_01595_amd as solon
     solon.lib()                                              # fail loudly if the HIP library is missing
+    for kv in args.tune:
+        key, val = kv.split("=")
+        solon.solon_tune(key, int(val))
 
     if args.calibrate_copy:
         import torch
@@ -156,6 +193,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.sweep == "paper":
+        sweep_paper_shapes(args.steps, args.warmup)
+        return
 
     main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
     others = []

@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __rest
 template <int M>
 static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
   constexpr int CH = (M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4);  // CH * M is a multiple of four
-  const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)u % 16 == 0);
+  // CH-float loads from the rows of R and 16-byte stores of u
+  const bool vec = ((uintptr_t)R % (4 * CH) == 0) && (ldr % CH == 0) && ((uintptr_t)u % 16 == 0);
   const int cap = solon_tuning("decode_blocks", 1 << 22);
   int64_t p_begin = 0;
   if constexpr (M != 1 && M != 2 && M != 4) {

@@ -68,7 +68,8 @@ __device__ __forceinline__ void store_chunks(float* dst, const float* z) {
 }
 
 // Fast path.  A thread owns UE consecutive coordinates (UE a multiple of m and of the 16-byte load width),
-// i.e. NC = UE / m whole chunks; blockIdx.y is the group.  Requires 16-byte aligned rows of G and of Z.
+// i.e. NC = UE / m whole chunks; blockIdx.y is the group.  Requires 16-byte aligned rows of G and rows of Z
+// aligned to the NC floats (at most four) a thread stores at once.
 template <int M, int UE, typename T, bool NT>
 __global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nunits) {
   constexpr int LV = load_traits<T>::LV;
@@ -247,7 +248,11 @@ int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, floa
   a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes;
   a.bat_off = plan->dev.bat_off; a.grp_batches = plan->dev.grp_batches; a.w = plan->dev.w;
   const size_t esz = plan->dtype == SOLON_BF16 ? 2 : 4;
-  const bool aligned = ((uintptr_t)G % 16 == 0) && ((size_t)ldg * esz % 16 == 0) && ((uintptr_t)Z % 16 == 0) && (ldz % 4 == 0);
+  // 16-byte loads need aligned rows of G; a thread of the fast kernels stores max(1, LV / m) floats per node
+  // at once (LV = elements per 16-byte load), so rows of Z need that alignment only
+  const int lv = plan->dtype == SOLON_BF16 ? 8 : 4;
+  const int zw = (lv % plan->m == 0) ? std::min(4, lv / plan->m) : 1;
+  const bool aligned = ((uintptr_t)G % 16 == 0) && ((size_t)ldg * esz % 16 == 0) && ((uintptr_t)Z % (4 * zw) == 0) && (ldz % zw == 0);
   if (plan->dtype == SOLON_BF16) return encode_by_m<uint16_t>(plan, a, aligned, st);
   return encode_by_m<float>(plan, a, aligned, st);
 }

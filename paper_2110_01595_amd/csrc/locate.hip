@@ -132,6 +132,7 @@ struct solve_smem {
 __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
   if (lane <= nc) {
     double sq = 0.0;
+#pragma unroll 4
     for (int i = 0; i < nr; ++i) sq = fma(S.A[i][lane], S.A[i][lane], sq);
     S.cn[lane] = sqrt(sq);
   }
@@ -141,6 +142,7 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
     bool dependent = row >= nr;
     double akk = 0.0, tail = 0.0, nrm = 0.0;
     if (!dependent) {
+#pragma unroll 4
       for (int i = row + 1; i < nr; ++i) tail = fma(S.A[i][k], S.A[i][k], tail);
       akk = S.A[row][k];
       nrm = sqrt(fma(akk, akk, tail));
@@ -155,9 +157,11 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
     const double vtv = fma(v0, v0, tail);
     if (lane > k && lane <= nc) {
       double dot = v0 * S.A[row][lane];
+#pragma unroll 4
       for (int i = row + 1; i < nr; ++i) dot = fma(S.A[i][k], S.A[i][lane], dot);
       const double cf = 2.0 * dot / vtv;
       S.A[row][lane] -= cf * v0;
+#pragma unroll 4
       for (int i = row + 1; i < nr; ++i) S.A[i][lane] = fma(-cf, S.A[i][k], S.A[i][lane]);
     }
     __syncthreads();
@@ -176,6 +180,7 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
         continue;
       }
       double acc = S.A[r][nc];
+#pragma unroll 4
       for (int j = k + 1; j < nc; ++j) acc = fma(-S.A[r][j], S.x[j], acc);
       S.x[k] = acc / S.A[r][k];
     }
@@ -201,83 +206,6 @@ __device__ int wave_rank(double v, bool active, int n, int lane) {
   return rank;
 }
 
-// The same least-squares solve with the matrix in registers: lane j holds column j (rows 0..NMAX-1, zero past
-// nr), the pivot column is broadcast lane to all with scalar reads, so no LDS round trips or barriers are needed.
-// Serves groups of up to NMAX nodes; the result goes to S.x like wave_least_squares'.
-template <int NMAX>
-__device__ void reg_least_squares(solve_smem& S, int nr, int nc, int lane) {
-  double col[NMAX];
-  double sq = 0.0;
-#pragma unroll
-  for (int i = 0; i < NMAX; ++i) {
-    col[i] = (i < nr && lane <= nc) ? S.A[i][lane] : 0.0;
-    sq = fma(col[i], col[i], sq);
-  }
-  const double cn = sqrt(sq);
-  int row = 0, myrow = -1;
-  for (int k = 0; k < nc; ++k) {
-    double v[NMAX];
-    double tail = 0.0, akk = 0.0;
-#pragma unroll
-    for (int i = 0; i < NMAX; ++i) {
-      v[i] = lane_bcast(col[i], k);
-      if (i > row) tail = fma(v[i], v[i], tail);
-      if (i == row) akk = v[i];
-    }
-    const double nrm = sqrt(fma(akk, akk, tail));
-    if (row >= nr || !(nrm > SOLON_RANK_TOL * lane_bcast(cn, k))) continue;  // dependent column: unknown stays zero
-    const double alpha = akk >= 0.0 ? -nrm : nrm;
-    const double v0 = akk - alpha;
-    const double vtv = fma(v0, v0, tail);
-    if (lane > k && lane <= nc) {
-      double dot = 0.0;
-#pragma unroll
-      for (int i = 0; i < NMAX; ++i) {
-        const double vi = (i == row) ? v0 : v[i];
-        if (i >= row) dot = fma(vi, col[i], dot);
-      }
-      const double cf = 2.0 * dot / vtv;
-#pragma unroll
-      for (int i = 0; i < NMAX; ++i) {
-        const double vi = (i == row) ? v0 : v[i];
-        if (i >= row) col[i] = fma(-cf, vi, col[i]);
-      }
-    }
-    if (lane == k) {
-#pragma unroll
-      for (int i = 0; i < NMAX; ++i)
-        if (i == row) col[i] = alpha;
-      myrow = row;
-    }
-    ++row;
-  }
-  // column-oriented back substitution: lane nc holds the transformed right-hand side
-  for (int k = nc - 1; k >= 0; --k) {
-    const int r = __builtin_amdgcn_readlane(myrow, k);
-    double xk = 0.0;
-    if (r >= 0) {
-      double sel = 0.0;
-#pragma unroll
-      for (int i = 0; i < NMAX; ++i)
-        if (i == r) sel = col[i];
-      xk = lane_bcast(sel, nc) / lane_bcast(sel, k);
-#pragma unroll
-      for (int i = 0; i < NMAX; ++i) {
-        const double rik = lane_bcast(col[i], k);  // R[i][k]
-        if (lane == nc && i < r) col[i] = fma(-xk, rik, col[i]);
-      }
-    }
-    if (lane == 0) S.x[k] = xk;
-  }
-  __syncthreads();
-}
-
-template <int NMAX>
-__device__ __forceinline__ void solve_least_squares(solve_smem& S, int nr, int nc, int lane) {
-  if constexpr (NMAX > 0) reg_least_squares<NMAX>(S, nr, nc, lane);
-  else wave_least_squares(S, nr, nc, lane);
-}
-
 struct solve_args {
   int s, m, run_locator;
   const int32_t* grp_off;
@@ -290,7 +218,6 @@ struct solve_args {
   float* dec_coef;
 };
 
-template <int NMAX>
 __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   __shared__ solve_smem S;
   const int g = blockIdx.x, lane = threadIdx.x;
@@ -356,7 +283,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
             }
           }
           __syncthreads();
-          solve_least_squares<NMAX>(S, nfin, nc, lane);
+          wave_least_squares(S, nfin, nc, lane);
           // |D(w_i)|: every corrupted point is a root of every solution's locator polynomial
           double dv = 0.0;
           if (pt) {
@@ -384,7 +311,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
           S.A[lane][m] = cand ? 0.0 : yl;
         }
         __syncthreads();
-        solve_least_squares<NMAX>(S, nfin, m, lane);
+        wave_least_squares(S, nfin, m, lane);
         bool flag = false;
         if (pt) {
           double pv = 0.0, t0 = 1.0, t1 = wl;
@@ -471,12 +398,7 @@ int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st) {
   a.s = plan->s; a.m = plan->m; a.run_locator = run_locator ? 1 : 0;
   a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
   a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
-  // columns in registers for groups of up to 16 nodes, the LDS-resident solve beyond (a 32-row register
-  // variant was measured slower than the LDS loops: its unrolled code is fetched cold by a single wavefront)
-  if (plan->max_group <= 16 && solon_tuning("solve_lds", 0) == 0)
-    hipLaunchKernelGGL(solve_kernel<16>, dim3(plan->q), dim3(64), 0, st, a);
-  else
-    hipLaunchKernelGGL(solve_kernel<0>, dim3(plan->q), dim3(64), 0, st, a);
+  hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
