@@ -94,9 +94,8 @@ __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __rest
     __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(&tile_out[4 * v]), reinterpret_cast<f32x4*>(dst + 4 * v));
 }
 
-template <int M>
+template <int M, int CH = ((M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4))>  // CH * M is a multiple of four
 static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
-  constexpr int CH = (M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4);  // CH * M is a multiple of four
   // CH-float loads from the rows of R and 16-byte stores of u
   const bool vec = ((uintptr_t)R % (4 * CH) == 0) && (ldr % CH == 0) && ((uintptr_t)u % 16 == 0);
   const int cap = solon_tuning("decode_blocks", 1 << 22);
@@ -125,6 +124,11 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
 }
 
 int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
+  if (plan->m == 4) {  // chunks per thread: two measured best on C4 / C5 (0.68 vs 0.70 ms with one, 0.95 ms with four)
+    const int ch = solon_tuning("decode_ch", 2);
+    if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, st);
+    if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, st);
+  }
   switch (plan->m) {
 #define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, st);
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)

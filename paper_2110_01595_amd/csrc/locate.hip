@@ -18,12 +18,13 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define SOLON_INV_NORM_MAX 1e6  // largest accepted infinity norm of the inverse m x m Vandermonde
 
 // ------------------------------------------------------------------------------------------------
-// Projection.  grid = (row bunches, column tiles); a thread keeps one fp64 accumulator per row of its
-// bunch and walks its tile's columns with 16-byte loads, so f is loaded once per RB rows of R.
+// Projection.  grid = (row bunches, column tiles); a tile is a contiguous run of `seg` 256-wide strips of
+// columns.  A thread keeps one fp64 accumulator per row of its bunch and walks its strips with 16-byte loads,
+// so f is loaded once per RB rows of R.  Blocks launched next to each other touch neighbouring addresses.
 template <int RB, bool VEC>
 __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ R, int64_t ldr, const float* __restrict__ f,
-                                                       int64_t d_c, int P, int rows_per_bunch, double* __restrict__ partials) {
-  const int bunch = blockIdx.x, tile = blockIdx.y, ntiles = gridDim.y;
+                                                       int64_t d_c, int P, int rows_per_bunch, int seg, double* __restrict__ partials) {
+  const int bunch = blockIdx.x, tile = blockIdx.y;
   const int row0 = bunch * rows_per_bunch;
   const int nrows = min(rows_per_bunch, P - row0);
   const int tid = threadIdx.x;
@@ -31,9 +32,12 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
 #pragma unroll
   for (int i = 0; i < RB; ++i) acc[i] = 0.0;
   const float* Rb = R + (int64_t)row0 * ldr;
+  const int64_t first = (int64_t)tile * seg * 256 + tid;
   if (VEC) {
     const int64_t nvec = d_c / 4;
-    for (int64_t u = (int64_t)tile * 256 + tid; u < nvec; u += (int64_t)ntiles * 256) {
+    for (int it = 0; it < seg; ++it) {
+      const int64_t u = first + (int64_t)it * 256;
+      if (u >= nvec) break;
       const f32x4 fv = *reinterpret_cast<const f32x4*>(f + 4 * u);
       const double f0 = fv.x, f1 = fv.y, f2 = fv.z, f3 = fv.w;
 #pragma unroll
@@ -55,7 +59,9 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
         if (i < nrows) acc[i] = fma(fc, (double)Rb[(int64_t)i * ldr + c], acc[i]);
     }
   } else {
-    for (int64_t c = (int64_t)tile * 256 + tid; c < d_c; c += (int64_t)ntiles * 256) {
+    for (int it = 0; it < seg; ++it) {
+      const int64_t c = first + (int64_t)it * 256;
+      if (c >= d_c) break;
       const double fc = f[c];
 #pragma unroll
       for (int i = 0; i < RB; ++i)
@@ -76,14 +82,17 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
   if (tid < nrows) partials[(int64_t)tile * P + row0 + tid] = ((sm[0][tid] + sm[1][tid]) + sm[2][tid]) + sm[3][tid];
 }
 
-// rho_j = sum over tiles of partials[tile][j], one wavefront per node, fixed order.
-__global__ __launch_bounds__(64) void reduce_kernel(const double* __restrict__ partials, int ntiles, int P, double* __restrict__ rho) {
-  const int j = blockIdx.x, lane = threadIdx.x;
+// rho_j = sum over tiles of partials[tile][j]: one block per node, strided partial sums, then a fixed tree.
+__global__ __launch_bounds__(256) void reduce_kernel(const double* __restrict__ partials, int ntiles, int P, double* __restrict__ rho) {
+  __shared__ double sm[4];
+  const int j = blockIdx.x, tid = threadIdx.x;
   double v = 0.0;
-  for (int t = lane; t < ntiles; t += 64) v += partials[(int64_t)t * P + j];
+  for (int t = tid; t < ntiles; t += 256) v += partials[(int64_t)t * P + j];
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-  if (lane == 0) rho[j] = v;
+  if ((tid & 63) == 0) sm[tid >> 6] = v;
+  __syncthreads();
+  if (tid == 0) rho[j] = ((sm[0] + sm[1]) + sm[2]) + sm[3];
 }
 
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
@@ -92,20 +101,23 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
   const int rows_per_bunch = (P + nbunch - 1) / nbunch;
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
   const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
-  const int cap = solon_tuning("project_blocks", 8192);
-  int64_t ntiles = std::max<int64_t>(1, (work + 255) / 256);
-  ntiles = std::min<int64_t>(ntiles, std::max(1, cap / nbunch));
-  ntiles = std::min<int64_t>(ntiles, SOLON_PROJ_MAX_TILES);
+  const int64_t strips = std::max<int64_t>(1, (work + 255) / 256);
+  // strips per tile: 4 to 16 (measured best: 16 once there are well over 6000 blocks, 4 for small inputs), and
+  // enough to keep the partial-sum table within its allocation
+  int64_t seg = solon_tuning("project_seg", 0);
+  if (seg <= 0) seg = std::min<int64_t>(16, std::max<int64_t>(4, strips * nbunch / 6000));
+  seg = std::max<int64_t>(seg, (strips + SOLON_PROJ_MAX_TILES - 1) / SOLON_PROJ_MAX_TILES);
+  const int64_t ntiles = (strips + seg - 1) / seg;
   plan->proj_tiles = (int)ntiles;
   dim3 grid((unsigned)nbunch, (unsigned)ntiles);
   if (vec)
     hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, true>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
-                       plan->dev.partials);
+                       (int)seg, plan->dev.partials);
   else
     hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, false>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
-                       plan->dev.partials);
+                       (int)seg, plan->dev.partials);
   SOLON_HIP(hipGetLastError());
-  hipLaunchKernelGGL(reduce_kernel, dim3(P), dim3(64), 0, st, plan->dev.partials, (int)ntiles, P, plan->dev.rho);
+  hipLaunchKernelGGL(reduce_kernel, dim3(P), dim3(256), 0, st, plan->dev.partials, (int)ntiles, P, plan->dev.rho);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }

@@ -10,7 +10,7 @@
 
 #define SOLON_MAX_M 16          // largest compression ratio with a compiled kernel
 #define SOLON_PROJ_ROWS 16      // rows of R one projection block accumulates at once
-#define SOLON_PROJ_MAX_TILES 2048
+#define SOLON_PROJ_MAX_TILES 8192
 
 // Device-side tables of a plan; every pointer points into the plan's single workspace allocation.
 struct solon_dev {
