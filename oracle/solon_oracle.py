@@ -233,14 +233,23 @@ def _locate_group_bw(wg, rho_g, s, m, tau, want_quotient=False):
         A, b = _locator_system(wf, y, m, s_eff)
         a = np.linalg.lstsq(A, b, rcond=RANK_RCOND)[0]
         D = np.concatenate([a[m + s_eff:], [1.0]])
-        # every corrupted point is a root of every solution's locator: the s smallest |D(w_i)|
+        # every corrupted point is a root of every solution's locator; when fewer than s nodes are corrupt the
+        # locator has further, arbitrary roots, so order the points by |D(w_i)| (corrupted ones come first)
         absD = np.abs(_cheb.chebval(wf, D))
-        cand = set(np.argsort(absD, kind="stable")[:s_eff].tolist())
+        order = np.argsort(absD, kind="stable")[:s_eff].tolist()
     else:
-        cand = set()
-    # P_j: the degree-(m-1) polynomial through the remaining points (equals N / D over the reals)
-    flagged, _, coef = _fit_and_test(wf, y, cand, m, tau)
-    if len(flagged) > s_eff:
+        order = []
+    # P_j: the degree-(m-1) polynomial through all points except the fewest leading locator roots that leave
+    # the rest consistent (equals N / D over the reals; leaving out no more points than necessary keeps honest
+    # points from being judged by an extrapolated fit)
+    flagged = None
+    for e in range(len(order) + 1):
+        cand = set(order[:e])
+        fl, _, coef = _fit_and_test(wf, y, cand, m, tau)
+        if all(i in cand for i in fl):
+            flagged = fl
+            break
+    if flagged is None:
         return None
     V = sorted(nonfinite + [int(fin[i]) for i in flagged])
     if want_quotient:

@@ -2,9 +2,9 @@
 //   1. rho_j = f R_j, accumulated in fp64 with a fixed reduction tree (project_kernel + reduce_kernel);
 //   2. per group, one wavefront builds and solves the error-locator system
 //        [W_{m+s-1}, -W_{s-1} .* (rho 1^T)] a = rho .* w^s
-//      (written in the Chebyshev basis, rows equilibrated), takes the s points where the locator
-//      polynomial is smallest as root candidates, refits the degree-(m-1) polynomial P_j through the
-//      other points and flags V = {i : |P_j(w_i) - rho_i| > tau * median|rho|};
+//      (written in the Chebyshev basis, rows equilibrated), orders the points by |D(w_i)| (corrupted points
+//      are roots of the locator D), fits the degree-(m-1) polynomial P_j through all points except the fewest
+//      leading roots that leave the rest consistent, and flags V = {i : |P_j(w_i) - rho_i| > tau * median|rho|};
 //   3. the same wavefront prepares psi (Lemma 2): m well-spread honest nodes of the group and the
 //      inverse of their m x m Vandermonde (Lagrange basis coefficients), left on the device for decode.
 #include <math.h>
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
         const int se = s - nnonfin;  // locator degree left for the finite points
         const bool pt = lane < nfin;
         const double yl = pt ? S.y[lane] : 0.0, wl = pt ? S.wv[lane] : 0.0;
-        bool cand = false;
+        int drank = 64;  // position of this point in the order of increasing |D(w_i)| (locator roots first)
         if (se > 0) {
           const int nn = m + se;      // numerator unknowns (Chebyshev coefficients 0 .. m+se-1)
           const int nc = nn + se;     // + locator unknowns (coefficients 0 .. se-1; T_se has coefficient one)
@@ -308,35 +308,44 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
             }
             dv = fabs(dv);
           }
-          const int drank = wave_rank(dv, pt, nfin, lane);
-          cand = pt && drank < se;
+          drank = wave_rank(dv, pt, nfin, lane);
         }
-        // P_j: least-squares polynomial of degree m-1 through the points that are not candidates
-        if (pt) {
-          double t0 = 1.0, t1 = wl;
-          for (int k = 0; k < m; ++k) {
-            S.A[lane][k] = cand ? 0.0 : t0;
-            const double t2 = 2.0 * wl * t1 - t0;
-            t0 = t1;
-            t1 = t2;
+        // P_j: least-squares polynomial of degree m-1 through all points except the fewest leading locator roots
+        // that leave the rest consistent.  When fewer than s nodes are corrupt the locator has further, arbitrary
+        // roots; leaving out no more points than necessary keeps honest points from being judged by an
+        // extrapolated fit.
+        unsigned long long flag_mask = 0;  // indexed by compacted position
+        bool consistent = false;
+        for (int ex = 0; ex <= se && !consistent; ++ex) {
+          const bool cand = pt && drank < ex;
+          if (pt) {
+            double t0 = 1.0, t1 = wl;
+            for (int k = 0; k < m; ++k) {
+              S.A[lane][k] = cand ? 0.0 : t0;
+              const double t2 = 2.0 * wl * t1 - t0;
+              t0 = t1;
+              t1 = t2;
+            }
+            S.A[lane][m] = cand ? 0.0 : yl;
           }
-          S.A[lane][m] = cand ? 0.0 : yl;
-        }
-        __syncthreads();
-        wave_least_squares(S, nfin, m, lane);
-        bool flag = false;
-        if (pt) {
-          double pv = 0.0, t0 = 1.0, t1 = wl;
-          for (int k = 0; k < m; ++k) {
-            pv = fma(S.x[k], t0, pv);
-            const double t2 = 2.0 * wl * t1 - t0;
-            t0 = t1;
-            t1 = t2;
+          __syncthreads();
+          wave_least_squares(S, nfin, m, lane);
+          bool flag = false;
+          if (pt) {
+            double pv = 0.0, t0 = 1.0, t1 = wl;
+            for (int k = 0; k < m; ++k) {
+              pv = fma(S.x[k], t0, pv);
+              const double t2 = 2.0 * wl * t1 - t0;
+              t0 = t1;
+              t1 = t2;
+            }
+            flag = !(fabs(pv - yl) <= SOLON_TAU);
           }
-          flag = !(fabs(pv - yl) <= SOLON_TAU);
+          flag_mask = __ballot(flag);
+          consistent = (flag_mask & ~__ballot(cand)) == 0;
+          __syncthreads();
         }
-        const unsigned long long flag_mask = __ballot(flag);  // indexed by compacted position
-        if (__popcll(flag_mask) > se) st = SOLON_E_DECODE;
+        if (!consistent) st = SOLON_E_DECODE;
         if (finite && ((flag_mask >> pos) & 1ull)) located = true;
       }
     }

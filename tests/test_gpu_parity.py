@@ -218,3 +218,67 @@ def test_linearity_of_encode_and_decode():
     solon.solon_encode(plan, G2, Z2)
     solon.solon_encode(plan, G1 * 0.5 - 2.0 * G2, Z3)
     assert so.rel_l2(Z3.cpu().numpy(), (0.5 * Z1 - 2.0 * Z2).cpu().numpy()) <= 1e-6
+
+
+def test_randomised_locate_against_oracle():
+    """Many small random instances: shapes, per-group numbers of corrupted nodes (0..s), attack kinds and strengths.
+    The located set must equal the oracle's on the same R; it must equal the planted set whenever every planted
+    deviation is far above the threshold (a deviation near tau * scale is ambiguous by definition)."""
+    rng = np.random.default_rng(2024)
+    shapes = [(7, 1, 1), (15, 1, 2), (31, 2, 2), (63, 3, 4), (100, 5, 4), (45, 2, 3), (100, 5, 10), (60, 4, 6)]
+    checked_planted = 0
+    for case in range(160):
+        P, s, m = shapes[case % len(shapes)]
+        d_c = int(rng.integers(600, 1500))
+        d = d_c * m - int(rng.integers(0, m))
+        plan = solon.Plan(P, s, m, d)
+        oplan = so.make_plan(P, s, m)
+        cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+        G = workloads.make_gradients(cfg, DEV, 5000 + case, d=d)
+        Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+        solon.solon_encode(plan, G, Z)
+        R = Z.clone()
+        planted = []
+        for g in range(oplan.q):
+            cnt = int(rng.integers(0, s + 1))
+            planted += rng.choice(oplan.nodes[g], size=cnt, replace=False).tolist()
+        planted = sorted(int(j) for j in planted)
+        for j in planted:
+            kind = int(rng.integers(0, 5))
+            if kind == 0:
+                R[j] *= float(rng.choice([-10.0, 3.0, 100.0, -0.5]))
+            elif kind == 1:
+                R[j] = torch.randn(plan.d_c, device=DEV) * float(Z[j].std()) * float(rng.choice([0.3, 1.0, 100.0]))
+            elif kind == 2:
+                R[j] += float(Z[j].abs().max()) * float(rng.choice([0.2, 5.0]))
+            elif kind == 3:
+                R[j] = Z[int(rng.integers(0, P))] if P > 1 else -Z[j]      # another node's honest message
+            else:
+                R[j] = float(rng.choice([0.0, -100.0, 1e30]))
+        f = workloads.make_projection(plan.d_c, DEV, 6000 + case)
+        say("random case", case, dict(P=P, s=s, m=m, d=d, planted=planted))
+        rho_ref = so.project(R.cpu().numpy(), f.cpu().numpy())
+        rho_hon = so.project(Z.cpu().numpy(), f.cpu().numpy())
+        try:
+            V_ref = so.locate(oplan, rho_ref, "bw")
+        except so.OracleError:
+            V_ref = None
+        try:
+            V, _ = solon.solon_locate(plan, R, f)
+        except solon.SolonError as e:
+            assert e.code == solon.SOLON_E_DECODE
+            V = None
+        clear = True
+        for g in range(oplan.q):
+            idx = oplan.nodes[g]
+            scale = np.median(np.abs(rho_hon[idx]))
+            for j in idx:
+                dev = abs(rho_ref[j] - rho_hon[j]) / scale
+                if j in planted and dev < 1e-2:
+                    clear = False
+        if clear:
+            assert V == V_ref == planted, (case, V, V_ref, planted)
+            checked_planted += 1
+        elif V_ref is not None and V is not None:
+            assert set(V) <= set(planted) and set(V_ref) <= set(planted)
+    assert checked_planted >= 120

@@ -358,3 +358,24 @@ def test_pins_catch_planted_mistakes(monkeypatch):
     assert so.rel_l2(so.decode(plan, bad, [], d), so.plain_sum(G)) > 1e-3
     f = 1.0 + rng.standard_normal(d // 2)
     assert so.locate(plan, so.project(bad, f), "bw") == [int(j)]      # and the locator sees it as corrupt
+
+
+@pytest.mark.parametrize("P,s,m", [(20, 5, 10), (16, 4, 8), (15, 5, 4), (11, 3, 4)])
+def test_fewer_than_s_corruptions_with_fp32_rounded_messages(P, s, m):
+    """Messages rounded to fp32 (as on the wire) and 0..s corrupted nodes: the located set is the planted one.
+    With fewer than s corrupted nodes the locator polynomial has spare, arbitrary roots; honest nodes that
+    happen to sit on them must not be flagged (they would be if P_j were fitted without them and extrapolated)."""
+    rng = np.random.default_rng(77 + P)
+    plan = so.make_plan(P, s, m)
+    d = 300 * m
+    wrong = 0
+    for trial in range(60):
+        G = rand_G(rng, P, d)
+        Z = so.encode(plan, G).astype(np.float32).astype(np.float64)
+        e = trial % (s + 1)
+        bad = sorted(rng.choice(P, size=e, replace=False).tolist())
+        R = corrupt(rng, Z, bad, "mix")
+        f = (1.0 + rng.standard_normal(Z.shape[1])).astype(np.float32)
+        V = so.locate(plan, so.project(R, f), "bw")
+        wrong += (V != bad)
+    assert wrong == 0
