@@ -218,6 +218,36 @@ __device__ int wave_rank(double v, bool active, int n, int lane) {
   return rank;
 }
 
+// Sum over the wavefront, identical bits in every lane (each butterfly step adds the same two numbers in both lanes).
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Value at this lane's point x of the least-squares polynomial of degree m-1 through the points (x, y) of the lanes
+// with `use` set.  Orthonormal polynomials of the discrete inner product over those points are generated by their
+// three-term recurrence (lane = point, a handful of wave sums per degree); no matrix is formed.
+__device__ double wave_polyfit(double x, double y, bool use, int m) {
+  const double wgt = use ? 1.0 : 0.0;
+  const double cnt = wave_sum(wgt);
+  if (!(cnt > 0.0)) return 0.0;
+  double p_prev = 0.0, p_cur = 1.0 / sqrt(cnt), fit = 0.0;
+  for (int k = 0; k < m; ++k) {
+    fit = fma(wave_sum(wgt * y * p_cur), p_cur, fit);
+    if (k + 1 == m) break;
+    const double xp = x * p_cur;
+    const double alpha = wave_sum(wgt * xp * p_cur);
+    const double beta = wave_sum(wgt * xp * p_prev);
+    const double q = xp - alpha * p_cur - beta * p_prev;
+    const double nrm = sqrt(wave_sum(wgt * q * q));
+    if (!(nrm > 1e-150)) break;  // fewer distinct points than coefficients: the remaining terms stay zero
+    p_prev = p_cur;
+    p_cur = q / nrm;
+  }
+  return fit;
+}
+
 struct solve_args {
   int s, m, run_locator;
   const int32_t* grp_off;
@@ -318,32 +348,10 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
         bool consistent = false;
         for (int ex = 0; ex <= se && !consistent; ++ex) {
           const bool cand = pt && drank < ex;
-          if (pt) {
-            double t0 = 1.0, t1 = wl;
-            for (int k = 0; k < m; ++k) {
-              S.A[lane][k] = cand ? 0.0 : t0;
-              const double t2 = 2.0 * wl * t1 - t0;
-              t0 = t1;
-              t1 = t2;
-            }
-            S.A[lane][m] = cand ? 0.0 : yl;
-          }
-          __syncthreads();
-          wave_least_squares(S, nfin, m, lane);
-          bool flag = false;
-          if (pt) {
-            double pv = 0.0, t0 = 1.0, t1 = wl;
-            for (int k = 0; k < m; ++k) {
-              pv = fma(S.x[k], t0, pv);
-              const double t2 = 2.0 * wl * t1 - t0;
-              t0 = t1;
-              t1 = t2;
-            }
-            flag = !(fabs(pv - yl) <= SOLON_TAU);
-          }
+          const double fitted = wave_polyfit(wl, yl, pt && !cand, m);
+          const bool flag = pt && !(fabs(fitted - yl) <= SOLON_TAU);
           flag_mask = __ballot(flag);
           consistent = (flag_mask & ~__ballot(cand)) == 0;
-          __syncthreads();
         }
         if (!consistent) st = SOLON_E_DECODE;
         if (finite && ((flag_mask >> pos) & 1ull)) located = true;
