@@ -166,6 +166,59 @@ def sweep_paper_shapes(steps, warmup):
             print(json.dumps({k: r[k] for k in keep}), flush=True)
 
 
+def sweep_repetition(steps, warmup):
+    """m = 1 (repetition code): the general locate + decode path next to the majority-vote decoder, same inputs."""
+    import torch
+
+    import paper_2110_01595_amd as solon
+    import workloads
+
+    dev = torch.device("cuda:0")
+    for P, s, d in ((63, 3, 25_600_000), (100, 5, 11_173_000), (15, 1, 11_200_000)):
+        cfg = dict(P=P, s=s, m=1, d=d, dtype="f32", dist="normal", sigma=0.01, attack="mix")
+        plan = solon.Plan(P, s, 1, d)
+        G = workloads.make_gradients(cfg, dev, 1)
+        ld = (d + 63) // 64 * 64
+        R = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d]
+        solon.solon_encode(plan, G, R)
+        byz = workloads.pick_byzantine(P, s, 3)
+        workloads.apply_attack(R, byz, "mix", 4)
+        f = workloads.make_projection(d, dev, 2)
+        u1 = torch.empty(d, dtype=torch.float32, device=dev)
+        u2 = torch.empty(d, dtype=torch.float32, device=dev)
+
+        def general():
+            solon.solon_locate(plan, R, f, want_host=False)
+            solon.solon_decode(plan, R, u1)
+
+        def majority():
+            solon.solon_decode_majority(plan, R, u2, want_host=False)
+
+        times = {}
+        for name, fn in (("locate+decode", general), ("majority", majority)):
+            for _ in range(warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            times[name] = e0.elapsed_time(e1) / steps
+        V1, _ = solon.solon_locate(plan, R, f)
+        V2 = solon.solon_decode_majority(plan, R, u2)
+        same = float((u1 - u2).norm() / u2.norm())
+        bytes_general = P * d * 4 + d * 4 + plan.q * d * 4 + d * 4
+        bytes_majority = P * d * 4 + d * 4
+        print(json.dumps(dict(workload="repetition_P%d_s%d_d%d" % (P, s, d), q=plan.q, ms=times,
+                              GBps={"locate+decode": bytes_general / times["locate+decode"] / 1e6,
+                                    "majority": bytes_majority / times["majority"] / 1e6},
+                              located_equal=(V1 == V2 == byz), rel_l2_between_paths=same)), flush=True)
+        del G, R, f, u1, u2
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -176,8 +229,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
                     help="launch-shape knob passed to solon_tune before the run (measurement aid; may be repeated)")
-    ap.add_argument("--sweep", choices=["paper"], default=None,
-                    help="instead of the headline line, run the paper's cost-study shapes and print one JSON line per shape")
+    ap.add_argument("--sweep", choices=["paper", "repetition"], default=None,
+                    help="instead of the headline line: 'paper' runs the paper's cost-study shapes, 'repetition' compares the "
+                         "m = 1 majority-vote decoder with the general path; one JSON line per shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain device copy of 4 GiB (reads 4 GiB, writes 4 GiB): the dispatch whose rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels")
@@ -203,6 +257,9 @@ def main():
 
     if args.sweep == "paper":
         sweep_paper_shapes(args.steps, args.warmup)
+        return
+    if args.sweep == "repetition":
+        sweep_repetition(args.steps, args.warmup)
         return
 
     main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline)

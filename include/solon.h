@@ -128,6 +128,22 @@ int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const float* f, 
 int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
                  void* hip_stream);
 
+/*
+ * Repetition-code decoder for m = 1 (every honest node of a group sends the group's gradient sum itself; the
+ * paper's appendix on the repetition code with its streaming majority vote): u[c] = sum over groups of the value
+ * that more than half of the group's nodes sent for coordinate c.  Needs no projection vector and no locate call;
+ * it is an independent check of solon_locate + solon_decode at m = 1 and reads R once.
+ *   R        device, P x d fp32 (d_c = d when m = 1), row stride ldr
+ *   u        device, d fp32
+ *   byz_idx  host int32[>= P] or NULL: receives the nodes that differ from their group's majority anywhere
+ *   n_byz    host int32* or NULL
+ * Returns SOLON_E_INVAL if the plan's m is not 1; SOLON_E_DECODE (through the host outputs or
+ * solon_decode_status) if some coordinate of some group has no majority value.  Asynchronous unless a host
+ * output pointer is given.
+ */
+int solon_decode_majority(solon_plan* plan, const float* R, int64_t ldr, float* u, int32_t* byz_idx, int32_t* n_byz,
+                          void* hip_stream);
+
 /* Waits for hip_stream and returns the status the last solon_locate / solon_decode on this plan left on the
  * device: SOLON_OK, SOLON_E_DECODE or SOLON_E_NUMERIC. */
 int solon_decode_status(solon_plan* plan, void* hip_stream);

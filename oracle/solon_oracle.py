@@ -328,6 +328,29 @@ def decode(plan, R, V, d):
     return u[:d]
 
 
+def decode_majority(plan, R, d):
+    """Repetition code (m = 1): per group and coordinate the value held by more than half of the group's nodes
+    (the paper's appendix on the repetition code), summed over groups.  The majority element of a list, if there
+    is one, is the middle element of the sorted list; that it really is a majority is then counted.
+    Returns (u, V) with V the nodes that differ from their group's majority anywhere."""
+    if plan.m != 1:
+        raise OracleError(E_INVAL, "majority decoding needs m = 1")
+    R = np.asarray(R, dtype=np.float64)
+    u = np.zeros(d, dtype=np.float64)
+    V = []
+    for g in range(plan.q):
+        idx = plan.nodes[g]
+        block = R[idx][:, :d]
+        with np.errstate(invalid="ignore"):
+            middle = np.sort(block, axis=0)[len(idx) // 2]       # NaNs sort last and never reach the middle of a majority
+            same = block == middle[None, :]
+        if np.any(2 * same.sum(axis=0) <= len(idx)):
+            raise OracleError(E_DECODE, "group %d: a coordinate has no majority value" % g)
+        u += middle
+        V.extend(int(idx[i]) for i in range(len(idx)) if not same[i].all())
+    return u, sorted(V)
+
+
 def rel_l2(a, b):
     a = np.asarray(a, dtype=np.float64)
     b = np.asarray(b, dtype=np.float64)

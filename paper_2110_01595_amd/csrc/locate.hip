@@ -432,7 +432,7 @@ int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st) {
   return SOLON_OK;
 }
 
-static int collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host /*P or null*/, double* rho_host /*P or null*/) {
+int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host /*P or null*/, double* rho_host /*P or null*/) {
   // staging layout: [double rho[P]] [int32 vmask[P]] [int32 status[q]]
   char* base = (char*)plan->pinned;
   double* h_rho = (double*)base;
@@ -476,7 +476,7 @@ extern "C" int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const
   if (rc != SOLON_OK) return rc;
   if (!byz_idx && !n_byz && !rho_out) return SOLON_OK;
   std::vector<int32_t> vm(plan->P);
-  rc = collect_status(plan, st, vm.data(), rho_out);
+  rc = solon_collect_status(plan, st, vm.data(), rho_out);
   if (rc == SOLON_E_HIP) return rc;
   int cnt = 0;
   for (int j = 0; j < plan->P; ++j) {
@@ -498,5 +498,5 @@ extern "C" int solon_decode_status(solon_plan* plan, void* hip_stream) {
     solon_set_error("solon_decode_status: the plan has no device workspace");
     return SOLON_E_HIP;
   }
-  return collect_status(plan, (hipStream_t)hip_stream, nullptr, nullptr);
+  return solon_collect_status(plan, (hipStream_t)hip_stream, nullptr, nullptr);
 }

@@ -1,0 +1,181 @@
+// Repetition-code decoder for compression ratio m = 1 (the special case in which W_j = I_d, so every honest node
+// of a group sends the group's gradient sum itself): per group and coordinate the value sent by the majority of
+// the group's nodes, found with the Boyer-Moore streaming majority vote (the paper's appendix on the repetition
+// code and its "Streaming Majority Vote" listing), then the sum over groups.  Nodes that differ from the majority
+// anywhere are reported as Byzantine.  One pass over R, one pass over u; no projection, no locator system.
+#include "solon_internal.h"
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__global__ void clear_flags_kernel(int32_t* vmask, int P, int32_t* status, int q) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P) vmask[i] = 0;
+  if (i < q) status[i] = SOLON_OK;
+}
+
+__device__ __forceinline__ void vote(float v, float& cand, int& count) {
+  if (count == 0) {
+    cand = v;
+    count = 1;
+  } else if (cand == v) {
+    ++count;
+  } else {
+    --count;
+  }
+}
+
+// A thread owns VEC consecutive coordinates (VEC = 4 with 16-byte loads when rows are aligned, else 1).
+template <int VEC>
+__global__ __launch_bounds__(256) void majority_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ grp_off,
+                                                        const int32_t* __restrict__ grp_nodes, float* __restrict__ u, int64_t d,
+                                                        int32_t* __restrict__ vmask, int32_t* __restrict__ status) {
+  const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t c0 = unit * VEC;
+  if (c0 >= d) return;
+  float total[VEC];
+#pragma unroll
+  for (int e = 0; e < VEC; ++e) total[e] = 0.0f;
+  for (int g = 0; g < q; ++g) {
+    const int n0 = grp_off[g], n1 = grp_off[g + 1];
+    float cand[VEC];
+    int count[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { cand[e] = 0.0f; count[e] = 0; }
+    for (int t = n0; t < n1; ++t) {  // first pass: streaming vote
+      const float* src = R + (int64_t)grp_nodes[t] * ldr + c0;
+      if (VEC == 4) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+        vote(v.x, cand[0], count[0]); vote(v.y, cand[1], count[1]); vote(v.z, cand[2], count[2]); vote(v.w, cand[3], count[3]);
+      } else {
+        vote(src[0], cand[0], count[0]);
+      }
+    }
+    int agree[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) agree[e] = 0;
+    for (int t = n0; t < n1; ++t) {  // second pass (cache hits): confirm the majority, mark the dissenters
+      const int j = grp_nodes[t];
+      const float* src = R + (int64_t)j * ldr + c0;
+      bool same = true;
+      if (VEC == 4) {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(src);
+        const bool s0 = v.x == cand[0], s1 = v.y == cand[1], s2 = v.z == cand[2], s3 = v.w == cand[3];
+        agree[0] += s0; agree[1] += s1; agree[2] += s2; agree[3] += s3;
+        same = s0 && s1 && s2 && s3;
+      } else {
+        same = src[0] == cand[0];
+        agree[0] += same;
+      }
+      if (!same) vmask[j] = 1;  // every writer stores the same value
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      if (2 * agree[e] <= n1 - n0) status[g] = SOLON_E_DECODE;  // no value is held by more than half of the group
+      total[e] += cand[e];
+    }
+  }
+  if (VEC == 4) {
+    f32x4 o = {total[0], total[1], total[2], total[3]};
+    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(u + c0));
+  } else {
+    u[c0] = total[0];
+  }
+}
+
+// Same result for groups of at most NMAX nodes and 16-byte aligned rows: the group's values stay in registers
+// between the vote and the confirmation pass (all loads are issued up front), and the vote is branch-free.
+template <int NMAX>
+__global__ __launch_bounds__(256) void majority_reg_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ grp_off,
+                                                            const int32_t* __restrict__ grp_nodes, float* __restrict__ u, int64_t d,
+                                                            int32_t* __restrict__ vmask, int32_t* __restrict__ status) {
+  const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t c0 = unit * 4;
+  if (c0 >= d) return;
+  f32x4 total = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 1
+  for (int g = 0; g < q; ++g) {
+    const int n0 = grp_off[g], n = grp_off[g + 1] - n0;
+    f32x4 v[NMAX];
+#pragma unroll
+    for (int t = 0; t < NMAX; ++t)
+      if (t < n) v[t] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(R + (int64_t)grp_nodes[n0 + t] * ldr + c0));
+    float cand[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int count[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < NMAX; ++t) {
+      if (t < n) {
+        const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool fresh = count[e] == 0, same = cand[e] == x[e];
+          cand[e] = fresh ? x[e] : cand[e];
+          count[e] = fresh ? 1 : (same ? count[e] + 1 : count[e] - 1);
+        }
+      }
+    }
+    int agree[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int t = 0; t < NMAX; ++t) {
+      if (t < n) {
+        const bool s0 = v[t].x == cand[0], s1 = v[t].y == cand[1], s2 = v[t].z == cand[2], s3 = v[t].w == cand[3];
+        agree[0] += s0; agree[1] += s1; agree[2] += s2; agree[3] += s3;
+        if (!(s0 && s1 && s2 && s3)) vmask[grp_nodes[n0 + t]] = 1;  // every writer stores the same value
+      }
+    }
+    if (2 * min(min(agree[0], agree[1]), min(agree[2], agree[3])) <= n) status[g] = SOLON_E_DECODE;
+    total += (f32x4){cand[0], cand[1], cand[2], cand[3]};
+  }
+  __builtin_nontemporal_store(total, reinterpret_cast<f32x4*>(u + c0));
+}
+
+extern "C" int solon_decode_majority(solon_plan* plan, const float* R, int64_t ldr, float* u, int32_t* byz_idx, int32_t* n_byz,
+                                     void* hip_stream) {
+  if (!plan || !R || !u) {
+    solon_set_error("solon_decode_majority: null argument");
+    return SOLON_E_INVAL;
+  }
+  if (plan->m != 1) {
+    solon_set_error("solon_decode_majority: the repetition-code decoder needs m = 1 (plan has m = %d)", plan->m);
+    return SOLON_E_INVAL;
+  }
+  if (ldr < plan->d) {
+    solon_set_error("solon_decode_majority: ldr %lld < d %lld", (long long)ldr, (long long)plan->d);
+    return SOLON_E_INVAL;
+  }
+  if (!plan->ws) {
+    solon_set_error("solon_decode_majority: the plan has no device workspace (no GPU at creation)");
+    return SOLON_E_HIP;
+  }
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int nflag = std::max(plan->P, plan->q);
+  hipLaunchKernelGGL(clear_flags_kernel, dim3((nflag + 255) / 256), dim3(256), 0, st, plan->dev.vmask, plan->P, plan->dev.status, plan->q);
+  SOLON_HIP(hipGetLastError());
+  const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)u % 16 == 0) && (plan->d % 4 == 0);
+  if (vec) {
+    const int64_t units = plan->d / 4;
+    const dim3 grid((unsigned)((units + 255) / 256));
+    if (plan->max_group <= 16)  // (an 8-node instance compiled to 234 registers per lane and ran slower than this one)
+      hipLaunchKernelGGL(majority_reg_kernel<16>, grid, dim3(256), 0, st, R, ldr, plan->q, plan->dev.grp_off, plan->dev.grp_nodes, u,
+                         plan->d, plan->dev.vmask, plan->dev.status);
+    else
+      hipLaunchKernelGGL(majority_kernel<4>, grid, dim3(256), 0, st, R, ldr, plan->q, plan->dev.grp_off, plan->dev.grp_nodes, u,
+                         plan->d, plan->dev.vmask, plan->dev.status);
+  } else {
+    hipLaunchKernelGGL(majority_kernel<1>, dim3((unsigned)((plan->d + 255) / 256)), dim3(256), 0, st, R, ldr, plan->q, plan->dev.grp_off,
+                       plan->dev.grp_nodes, u, plan->d, plan->dev.vmask, plan->dev.status);
+  }
+  SOLON_HIP(hipGetLastError());
+  if (!byz_idx && !n_byz) return SOLON_OK;
+  std::vector<int32_t> vm(plan->P);
+  const int rc = solon_collect_status(plan, st, vm.data(), nullptr);
+  if (rc == SOLON_E_HIP) return rc;
+  int cnt = 0;
+  for (int j = 0; j < plan->P; ++j) {
+    if (plan->group_of_node[j] >= 0 && vm[j]) {
+      if (byz_idx) byz_idx[cnt] = j;
+      ++cnt;
+    }
+  }
+  if (n_byz) *n_byz = cnt;
+  return rc;
+}

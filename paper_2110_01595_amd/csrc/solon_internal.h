@@ -57,4 +57,6 @@ int solon_tuning(const char* key, int fallback);
 int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st);
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st);
 int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st);
+// waits for the stream, copies status (and optionally the located mask and rho) to the host, returns the worst group status
+int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host, double* rho_host);
 int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st);

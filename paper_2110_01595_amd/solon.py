@@ -18,7 +18,8 @@ SOLON_Q_GROUPS, SOLON_Q_REDUNDANCY, SOLON_Q_MESSAGE_LEN, SOLON_Q_MAX_GROUP, SOLO
 
 EXPORTS = [
     "solon_plan_create", "solon_plan_destroy", "solon_plan_query", "solon_plan_groups", "solon_plan_points",
-    "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_decode_status", "solon_tune",
+    "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_decode_majority", "solon_decode_status",
+    "solon_tune",
     "solon_last_error",
 ]
 
@@ -61,6 +62,8 @@ def lib():
     L.solon_locate.restype = i32
     L.solon_decode.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.solon_decode.restype = i32
+    L.solon_decode_majority.argtypes = [vp, vp, i64, vp, vp, vp, vp]
+    L.solon_decode_majority.restype = i32
     L.solon_decode_status.argtypes = [vp, vp]
     L.solon_decode_status.restype = i32
     L.solon_tune.argtypes = [ctypes.c_char_p, i32]
@@ -174,6 +177,18 @@ def solon_decode(plan, R, u, byz=None, stream=None):
     else:
         idx = np.ascontiguousarray(byz, dtype=np.int32)
         _check(lib().solon_decode(plan._h, _dev_ptr(R), R.stride(0), _np_ptr(idx), len(idx), _dev_ptr(u), _stream(stream)))
+
+
+def solon_decode_majority(plan, R, u, want_host=True, stream=None):
+    """m = 1 only.  Returns the sorted list of nodes that differ from their group's majority (None if want_host=False)."""
+    assert R.is_cuda and u.is_cuda and R.stride(1) == 1 and u.is_contiguous()
+    if not want_host:
+        _check(lib().solon_decode_majority(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(u), None, None, _stream(stream)))
+        return None
+    idx = np.full(plan.P, -1, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(lib().solon_decode_majority(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(u), _np_ptr(idx), ctypes.byref(n), _stream(stream)))
+    return idx[: n.value].tolist()
 
 
 def solon_decode_status(plan, stream=None):
