@@ -2,6 +2,7 @@
 // Y_j 1_P is formed once in registers, and each node j of the group writes
 // z_j[p] = sum_l w_j^l * ybar[p m + l]  (row p of W_j = I_{d_c} (x) [1, w_j, .., w_j^{m-1}]).
 // One pass over G, one pass over Z; HBM-bound, no matrix cores (inner dimension <= group size).
+#include "grid_phase.h"
 #include "solon_internal.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -108,6 +109,74 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nun
   }
 }
 
+// Phase-separated fast path for large inputs.  A persistent grid (as many blocks as are resident at once) walks
+// the groups; for each it alternates a chip-wide read phase - every thread sums U units of all the group's
+// gradient rows into registers - and a write phase - the Horner evaluations of all the group's nodes for those
+// units - with an alignment point between them, so that HBM sees long runs of reads and long runs of writes
+// instead of their mixture.  For a fixed i the grid covers one contiguous span of every row.  Same arithmetic,
+// same order of additions as encode_vec_kernel.
+// units a thread of the phase-separated kernel keeps in registers: as many as leave eight waves per SIMD resident
+template <typename T> struct phase_units;
+template <> struct phase_units<float> { static constexpr int U = 6; };
+template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
+
+template <int M, typename T>
+__global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit) {
+  constexpr int LV = load_traits<T>::LV;
+  constexpr int NC = LV / M;
+  constexpr int U = phase_units<T>::U;
+  const T* G = static_cast<const T*>(a.G);
+  const int64_t span = (int64_t)gridDim.x * blockDim.x;
+  const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_phase = span * U;
+  const int nphase = (int)((nunits + per_phase - 1) / per_phase);
+  uint32_t nbar = 0;
+  for (int g = 0; g < q; ++g) {
+    const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+    const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+    for (int ph = 0; ph < nphase; ++ph) {
+      const int64_t u0 = (int64_t)ph * per_phase + gtid;
+      float acc[U][LV];
+#pragma unroll
+      for (int i = 0; i < U; ++i)
+#pragma unroll
+        for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
+      for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+        const T* src = G + (int64_t)a.grp_batches[k] * a.ldg;
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          int64_t u = u0 + (int64_t)i * span;
+          u = u < nunits ? u : nunits - 1;  // past the end: reload the last unit (in bounds, result unused) rather than branch
+          load_add<true>(src + u * LV, acc[i]);
+        }
+      }
+      solon_phase_align(sync, ++nbar, spin_limit);
+      for (int t = n0; t < n1; ++t) {
+        const int j = a.grp_nodes[t];
+        const float wj = a.w[j];
+        float* zrow = a.Z + (int64_t)j * a.ldz;
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          const int64_t u = u0 + (int64_t)i * span;
+          if (u < nunits) {
+            float z[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) {
+              float h = acc[i][c * M + M - 1];
+#pragma unroll
+              for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, acc[i][c * M + l]);  // Horner in w_j
+              z[c] = h;
+            }
+            store_chunks<NC, true>(zrow + u * NC, z);
+          }
+        }
+      }
+      solon_phase_align(sync, ++nbar, spin_limit);
+    }
+  }
+  solon_phase_exit(sync);
+}
+
 // General path: any alignment, any d; a thread owns one chunk p in [p0, p1).
 template <int M, typename T>
 __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p0, int64_t p1) {
@@ -201,7 +270,22 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
   if (aligned && solon_tuning("encode_force_generic", 0) == 0) {
     if constexpr (LV % M == 0) {  // m divides the load width: one 16-byte load per row and thread
       const int64_t nunits = plan->d / LV;
-      if (nunits > 0) {
+      // phase-separated persistent grid when every group keeps the whole chip busy for several phases
+      int phase_grid = 0;
+      const int want_phase = solon_tuning("encode_phase", -1);
+      if (nunits > 0 && want_phase != 0) {
+        phase_grid = solon_resident_grid((const void*)encode_phase_kernel<M, T>, 1024);
+        const int grid_cap = solon_tuning("encode_phase_grid", 0);  // tests: a few blocks make many phases of a small input
+        if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
+        const int64_t per_phase = (int64_t)phase_grid * 1024 * phase_units<T>::U;
+        if (want_phase < 0 && nunits < 2 * per_phase) phase_grid = 0;
+      }
+      if (phase_grid > 0) {
+        hipLaunchKernelGGL((encode_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), 0, st, a, nunits, q,
+                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+        SOLON_HIP(hipGetLastError());
+        done_chunks = nunits * (LV / M);
+      } else if (nunits > 0) {
         int64_t bx = std::min<int64_t>((nunits + threads - 1) / threads, std::max(1, cap));
         dim3 grid((unsigned)bx, (unsigned)q);
         if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, true>), grid, dim3(threads), 0, st, a, nunits);

@@ -44,6 +44,24 @@ int solon_tuning(const char* key, int fallback) {
   return it == g_tune.end() ? fallback : it->second;
 }
 
+// ---------------------------------------------------------------- persistent-grid size
+int solon_resident_grid(const void* kernel, int threads) {
+  static std::mutex mu;
+  static std::map<const void*, int> cache;
+  std::lock_guard<std::mutex> lk(mu);
+  auto it = cache.find(kernel);
+  if (it != cache.end()) return it->second;
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    return 0;
+  }
+  const int grid = cus * per_cu;
+  cache[kernel] = grid;
+  return grid;
+}
+
 // ---------------------------------------------------------------- evaluation points
 extern "C" int solon_default_points(int r_g, float* out) {
   if (r_g < 1 || !out) {
@@ -213,6 +231,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   const size_t o_status = take(sizeof(int32_t) * q);
   const size_t o_rows = take(sizeof(int32_t) * q * m);
   const size_t o_coef = take(sizeof(float) * q * m * m);
+  const size_t o_sync = take(sizeof(uint32_t) * SOLON_SYNC_WORDS);
   p->ws_bytes = off;
   hipError_t e = hipMalloc(&p->ws, p->ws_bytes);
   if (e != hipSuccess) {
@@ -231,6 +250,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->dev.status = (int32_t*)(base + o_status);
   p->dev.dec_rows = (int32_t*)(base + o_rows);
   p->dev.dec_coef = (float*)(base + o_coef);
+  p->dev.grid_sync = (uint32_t*)(base + o_sync);
   p->pinned_bytes = align_up(sizeof(double) * P + sizeof(int32_t) * (P + q), 256);
   e = hipHostMalloc(&p->pinned, p->pinned_bytes, hipHostMallocDefault);
   if (e != hipSuccess) {

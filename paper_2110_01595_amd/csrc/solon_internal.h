@@ -11,6 +11,7 @@
 #define SOLON_MAX_M 16          // largest compression ratio with a compiled kernel
 #define SOLON_PROJ_ROWS 16      // rows of R one projection block accumulates at once
 #define SOLON_PROJ_MAX_TILES 8192
+#define SOLON_SYNC_WORDS 512     // 8 counters 128 bytes apart, one grid-wide counter, one exit counter
 
 // Device-side tables of a plan; every pointer points into the plan's single workspace allocation.
 struct solon_dev {
@@ -25,6 +26,7 @@ struct solon_dev {
   int32_t* status;       // [q] per-group status of the last locate / decode set-up
   int32_t* dec_rows;     // [q * m] rows of R chosen for psi
   float* dec_coef;       // [q][m][m] psi's coefficients T[g][l][t], stored as [g][t][l]
+  uint32_t* grid_sync;   // [SOLON_SYNC_WORDS] arrival counters of the phase-separated kernels; zero between launches
 };
 
 struct solon_plan {
@@ -52,6 +54,9 @@ int solon_hip_fail(hipError_t e, const char* what);
   } while (0)
 
 int solon_tuning(const char* key, int fallback);
+// Number of blocks of `threads` threads of `kernel` that the current device keeps resident at once (0 on error);
+// cached per kernel.
+int solon_resident_grid(const void* kernel, int threads);
 
 // launchers (defined next to their kernels)
 int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st);

@@ -54,6 +54,28 @@ def test_full_size_config(name, u_tol):
         assert so.rel_l2(Zh, Z_ref) <= 1e-6, (name, p0)
         assert np.abs(Zh - Z_ref).max() <= 4e-6 * (np.abs(Z_ref).max() + 1e-30)
 
+    # encode, every element: the defining sum written with torch ops in fp64 on the device (no oracle at this size)
+    wpts = torch.tensor(np.asarray(oplan.w, dtype=np.float64), device=DEV)
+    num = den = 0.0
+    worst = 0.0
+    blk = 1 << 21
+    for p0 in range(0, d_c, blk):
+        p1 = min(d_c, p0 + blk)
+        c0, c1 = p0 * m, min(d, p1 * m)
+        for g in range(oplan.q):
+            ybar = G[oplan.batches[g].tolist(), c0:c1].sum(dim=0, dtype=torch.float64)
+            if ybar.numel() < (p1 - p0) * m:
+                ybar = torch.nn.functional.pad(ybar, (0, (p1 - p0) * m - ybar.numel()))
+            ybar = ybar.view(p1 - p0, m)
+            for j in oplan.nodes[g].tolist():
+                ref = (ybar * wpts[j] ** torch.arange(m, dtype=torch.float64, device=DEV)).sum(dim=1)
+                diff = Z[j, p0:p1].double() - ref
+                num += float((diff * diff).sum())
+                den += float((ref * ref).sum())
+                worst = max(worst, float(diff.abs().max()) / (float(ref.abs().max()) + 1e-30))
+    say("  rel_l2(Z, definition) over all P x d_c = %.3e, worst row window %.3e" % ((num / den) ** 0.5, worst), round(time.time() - t_start, 1), "s")
+    assert (num / den) ** 0.5 <= 1e-6 and worst <= 4e-6
+
     byz = workloads.pick_byzantine(P, s, sd["byz"])
     R = Z                                                   # attack in place: Z is not needed any more
     workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])

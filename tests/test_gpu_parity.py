@@ -129,6 +129,48 @@ def test_unaligned_rows_use_general_kernels():
     run_case(100, 5, 4, 9_999, pad=2, dtype="bf16", seed=7)
 
 
+@pytest.mark.parametrize("grid", [3, 0])
+def test_phase_separated_encode(grid):
+    """The persistent, phase-separated encoder forced onto small inputs: with three blocks a group takes several
+    read / write phases and the last one is ragged; with the full grid most threads have nothing to do."""
+    solon.solon_tune("encode_phase", 1)
+    solon.solon_tune("encode_phase_grid", grid)
+    try:
+        run_case(63, 3, 4, 131_075, seed=21)                                   # fp32, 11/10-node groups, tail chunk
+        run_case(15, 1, 2, 40_002, seed=22)
+        run_case(7, 1, 1, 70_001, seed=23)
+        run_case(100, 5, 4, 200_008, dtype="bf16", attack="mix", dist="student3", sigma=1e-3, seed=24)
+        run_case(24, 2, 8, 64_008, dtype="bf16", seed=25)
+        run_case(15, 1, 2, 40_002, dtype="bf16", seed=26)
+        run_case(7, 1, 1, 20_001, dtype="bf16", seed=27)
+        run_case(4, 1, 2, 9, seed=28)                                          # two units in all
+        gon = [0] * 5 + [-1] + [1] * 6                                          # an idle node: its row stays untouched
+        run_case(12, 1, 2, 50_000, group_of_node=gon, group_of_batch=[0] * 6 + [1] * 6, seed=29)
+    finally:
+        solon.solon_tune("encode_phase", -1)
+        solon.solon_tune("encode_phase_grid", 0)
+
+
+def test_phase_separated_encode_equals_flat_kernel_bitwise():
+    """Both fast encoders add the gradients in batch order and evaluate the same Horner scheme: identical bits."""
+    cfg = dict(P=63, d=3_000_000, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(63, 3, 4, cfg["d"])
+    G = workloads.make_gradients(cfg, DEV, 31, d=cfg["d"])
+    Za = torch.zeros((63, plan.d_c), dtype=torch.float32, device=DEV)
+    Zb = torch.zeros_like(Za)
+    try:
+        solon.solon_tune("encode_phase", 0)
+        solon.solon_encode(plan, G, Za)
+        solon.solon_tune("encode_phase", 1)
+        for _ in range(3):                                                     # the arrival counters reset themselves between launches
+            Zb.zero_()
+            solon.solon_encode(plan, G, Zb)
+            torch.cuda.synchronize()
+            assert torch.equal(Za, Zb)
+    finally:
+        solon.solon_tune("encode_phase", -1)
+
+
 def test_decode_with_host_supplied_set():
     run_case(31, 2, 2, 20_000, attack="noise100", decode_from_host=True, seed=8)
 
