@@ -2,6 +2,7 @@
 //   u[p m + l] = sum_g sum_t T[g][l][t] * R[U_g[t]][p]
 // with U_g the m honest nodes chosen for group g and T[g] the inverse of their m x m Vandermonde,
 // both left in the plan's workspace by the locator wavefront.  Reads q m rows of R once, writes u once.
+#include "grid_phase.h"
 #include "solon_internal.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -64,6 +65,75 @@ __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict_
   }
 }
 
+// Phase-separated fast path for large inputs and m in {1, 2, 4} (see grid_phase.h): a persistent grid alternates
+// a chip-wide read phase - every thread recombines U units of 4 / m chunks each from the q m chosen rows, in
+// registers - and a write phase that stores the 4 U output coordinates as U coalesced 16-byte stores.  Same
+// arithmetic and order of additions as recombine_kernel.
+// units per thread that keep eight waves per SIMD resident without spills
+constexpr int recombine_phase_units(int m) { return m == 4 ? 8 : m == 2 ? 6 : 8; }
+
+template <int M>
+__global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* __restrict__ R, int64_t ldr, int q,
+                                                                   const int32_t* __restrict__ rows, const float* __restrict__ coef,
+                                                                   float* __restrict__ u, int64_t nunits, uint32_t* sync, int spin_limit) {
+  constexpr int CH = 4 / M;
+  constexpr int U = recombine_phase_units(M);
+  typedef typename chunk_vec<CH>::type vt;
+  // unit indices fit 32 bits (checked by the launcher), which keeps the U positions of a thread in U registers
+  const uint32_t span = gridDim.x * blockDim.x;
+  const uint32_t gtid = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t per_phase = span * U;
+  const uint32_t last = (uint32_t)nunits - 1u;
+  const int nphase = (int)((nunits + per_phase - 1) / per_phase);
+  uint32_t nbar = 0;
+  for (int ph = 0; ph < nphase; ++ph) {
+    const uint32_t u0 = (uint32_t)ph * per_phase + gtid;
+    float out[U][4];
+#pragma unroll
+    for (int i = 0; i < U; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[i][e] = 0.0f;
+    for (int g = 0; g < q; ++g) {
+#pragma unroll
+      for (int t = 0; t < M; ++t) {
+        const float* src = R + (int64_t)rows[g * M + t] * ldr;
+        float cf[M];
+#pragma unroll
+        for (int l = 0; l < M; ++l) cf[l] = coef[(g * M + t) * M + l];
+        vt x[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          uint32_t unit = u0 + (uint32_t)i * span;
+          unit = unit < last ? unit : last;  // past the end: reload the last unit (in bounds, result unused)
+          x[i] = __builtin_nontemporal_load(reinterpret_cast<const vt*>(src + (int64_t)unit * CH));
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          float v[CH];
+          if constexpr (CH == 1) { v[0] = x[i]; }
+          else if constexpr (CH == 2) { v[0] = x[i].x; v[1] = x[i].y; }
+          else { v[0] = x[i].x; v[1] = x[i].y; v[2] = x[i].z; v[3] = x[i].w; }
+#pragma unroll
+          for (int l = 0; l < M; ++l)
+#pragma unroll
+            for (int c = 0; c < CH; ++c) out[i][c * M + l] = fmaf(cf[l], v[c], out[i][c * M + l]);
+        }
+      }
+    }
+    solon_phase_align(sync, ++nbar, spin_limit);
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const uint32_t unit = u0 + (uint32_t)i * span;
+      if (unit <= last) {
+        f32x4 o = {out[i][0], out[i][1], out[i][2], out[i][3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(u + (int64_t)unit * 4));
+      }
+    }
+    solon_phase_align(sync, ++nbar, spin_limit);
+  }
+  solon_phase_exit(sync);
+}
+
 // Tiled path for compression ratios other than 1, 2, 4.  A block owns 256 consecutive chunks: each thread
 // recombines its chunk from coalesced 4-byte loads, the 256 m results pass through LDS and leave as coalesced
 // 16-byte stores.
@@ -107,6 +177,26 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
                          plan->dev.dec_coef, u);
       SOLON_HIP(hipGetLastError());
       p_begin = ntiles * 256;
+    }
+  }
+  if constexpr (M == 1 || M == 2 || M == 4) {
+    // units of four output coordinates that lie entirely below d; rows of R aligned for (4 / m)-float loads
+    constexpr int PCH = 4 / M;
+    const int64_t punits = plan->d / 4;
+    const bool pvec = ((uintptr_t)R % (4 * PCH) == 0) && (ldr % PCH == 0) && ((uintptr_t)u % 16 == 0);
+    const int want_phase = solon_tuning("decode_phase", -1);
+    int phase_grid = 0;
+    if (pvec && punits > 0 && punits < (int64_t)1 << 30 && want_phase != 0) {
+      phase_grid = solon_resident_grid((const void*)recombine_phase_kernel<M>, 1024);
+      const int grid_cap = solon_tuning("decode_phase_grid", 0);
+      if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
+      if (want_phase < 0 && punits < 4 * (int64_t)phase_grid * 1024 * recombine_phase_units(M)) phase_grid = 0;  // measured: no gain below four phases
+    }
+    if (phase_grid > 0) {
+      hipLaunchKernelGGL((recombine_phase_kernel<M>), dim3((unsigned)phase_grid), dim3(1024), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+      SOLON_HIP(hipGetLastError());
+      p_begin = punits * PCH;  // a multiple of every CH used below
     }
   }
   if (p_begin >= plan->d_c) return SOLON_OK;

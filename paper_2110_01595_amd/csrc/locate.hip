@@ -18,20 +18,25 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define SOLON_INV_NORM_MAX 1e6  // largest accepted infinity norm of the inverse m x m Vandermonde
 
 // ------------------------------------------------------------------------------------------------
-// Projection.  grid = (row bunches, column tiles); a tile is a contiguous run of `seg` 256-wide strips of
-// columns.  A thread keeps one fp64 accumulator per row of its bunch and walks its strips with 16-byte loads,
-// so f is loaded once per RB rows of R.  Blocks launched next to each other touch neighbouring addresses.
+// Projection.  grid = (row bunches, column tiles); a bunch is RB consecutive rows of R (the last bunch may hold
+// fewer), a tile a contiguous run of `seg` 256-wide strips of columns.  A thread keeps one fp64 accumulator per
+// row of its bunch and walks its strips with 16-byte loads, so f is loaded once per RB rows of R.  All RB loads of
+// a strip are issued back to back with no branch between them: a bunch with fewer rows re-reads its last row
+// (in bounds, served by the cache) and drops those sums.
 template <int RB, bool VEC>
 __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ R, int64_t ldr, const float* __restrict__ f,
-                                                       int64_t d_c, int P, int rows_per_bunch, int seg, double* __restrict__ partials) {
+                                                       int64_t d_c, int P, int seg, double* __restrict__ partials) {
   const int bunch = blockIdx.x, tile = blockIdx.y;
-  const int row0 = bunch * rows_per_bunch;
-  const int nrows = min(rows_per_bunch, P - row0);
+  const int row0 = bunch * RB;
+  const int nrows = min(RB, P - row0);
   const int tid = threadIdx.x;
   double acc[RB];
+  const float* rp[RB];
 #pragma unroll
-  for (int i = 0; i < RB; ++i) acc[i] = 0.0;
-  const float* Rb = R + (int64_t)row0 * ldr;
+  for (int i = 0; i < RB; ++i) {
+    acc[i] = 0.0;
+    rp[i] = R + (int64_t)(row0 + min(i, nrows - 1)) * ldr;
+  }
   const int64_t first = (int64_t)tile * seg * 256 + tid;
   if (VEC) {
     const int64_t nvec = d_c / 4;
@@ -39,24 +44,23 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
       const int64_t u = first + (int64_t)it * 256;
       if (u >= nvec) break;
       const f32x4 fv = *reinterpret_cast<const f32x4*>(f + 4 * u);
+      f32x4 rv[RB];
+#pragma unroll
+      for (int i = 0; i < RB; ++i) rv[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(rp[i] + 4 * u));
       const double f0 = fv.x, f1 = fv.y, f2 = fv.z, f3 = fv.w;
 #pragma unroll
       for (int i = 0; i < RB; ++i) {
-        if (i < nrows) {
-          const f32x4 rv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(Rb + (int64_t)i * ldr + 4 * u));
-          acc[i] = fma(f0, (double)rv.x, acc[i]);
-          acc[i] = fma(f1, (double)rv.y, acc[i]);
-          acc[i] = fma(f2, (double)rv.z, acc[i]);
-          acc[i] = fma(f3, (double)rv.w, acc[i]);
-        }
+        acc[i] = fma(f0, (double)rv[i].x, acc[i]);
+        acc[i] = fma(f1, (double)rv[i].y, acc[i]);
+        acc[i] = fma(f2, (double)rv[i].z, acc[i]);
+        acc[i] = fma(f3, (double)rv[i].w, acc[i]);
       }
     }
     if (tile == 0 && tid < (int)(d_c - nvec * 4)) {  // fewer than four trailing columns
       const int64_t c = nvec * 4 + tid;
       const double fc = f[c];
 #pragma unroll
-      for (int i = 0; i < RB; ++i)
-        if (i < nrows) acc[i] = fma(fc, (double)Rb[(int64_t)i * ldr + c], acc[i]);
+      for (int i = 0; i < RB; ++i) acc[i] = fma(fc, (double)rp[i][c], acc[i]);
     }
   } else {
     for (int it = 0; it < seg; ++it) {
@@ -64,8 +68,7 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
       if (c >= d_c) break;
       const double fc = f[c];
 #pragma unroll
-      for (int i = 0; i < RB; ++i)
-        if (i < nrows) acc[i] = fma(fc, (double)Rb[(int64_t)i * ldr + c], acc[i]);
+      for (int i = 0; i < RB; ++i) acc[i] = fma(fc, (double)rp[i][c], acc[i]);
     }
   }
   // fixed-order reduction: butterfly inside each wavefront, then the four wavefronts in order
@@ -95,10 +98,21 @@ __global__ __launch_bounds__(256) void reduce_kernel(const double* __restrict__ 
   if (tid == 0) rho[j] = ((sm[0] + sm[1]) + sm[2]) + sm[3];
 }
 
+template <int RB>
+static void project_launch(bool vec, dim3 grid, hipStream_t st, const float* R, int64_t ldr, const float* f, int64_t d_c, int P, int seg,
+                           double* partials) {
+  if (vec) hipLaunchKernelGGL((project_kernel<RB, true>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, partials);
+  else hipLaunchKernelGGL((project_kernel<RB, false>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, partials);
+}
+
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
   const int P = plan->P;
-  const int nbunch = (P + SOLON_PROJ_ROWS - 1) / SOLON_PROJ_ROWS;
-  const int rows_per_bunch = (P + nbunch - 1) / nbunch;
+  // rows per bunch: the fewest bunches of at most 21 rows (the most that leave four waves per SIMD resident; measured on
+  // P = 100: 20 rows 6.65 TB/s, 25 rows 5.9 TB/s), of equal size where P allows
+  const int rb_max = std::max(1, std::min(SOLON_PROJ_ROWS, solon_tuning("project_rows", 21)));
+  const int nbunch0 = (P + rb_max - 1) / rb_max;
+  const int rb = (P + nbunch0 - 1) / nbunch0;
+  const int nbunch = (P + rb - 1) / rb;
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
   const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
   const int64_t strips = std::max<int64_t>(1, (work + 255) / 256);
@@ -110,12 +124,17 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
   const int64_t ntiles = (strips + seg - 1) / seg;
   plan->proj_tiles = (int)ntiles;
   dim3 grid((unsigned)nbunch, (unsigned)ntiles);
-  if (vec)
-    hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, true>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
-                       (int)seg, plan->dev.partials);
-  else
-    hipLaunchKernelGGL((project_kernel<SOLON_PROJ_ROWS, false>), grid, dim3(256), 0, st, R, ldr, f, plan->d_c, P, rows_per_bunch,
-                       (int)seg, plan->dev.partials);
+  switch (rb) {
+#define SOLON_CASE(N) case N: project_launch<N>(vec, grid, st, R, ldr, f, plan->d_c, P, (int)seg, plan->dev.partials); break;
+    SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
+    SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
+    SOLON_CASE(17) SOLON_CASE(18) SOLON_CASE(19) SOLON_CASE(20) SOLON_CASE(21) SOLON_CASE(22) SOLON_CASE(23) SOLON_CASE(24)
+    SOLON_CASE(25) SOLON_CASE(26) SOLON_CASE(27) SOLON_CASE(28) SOLON_CASE(29) SOLON_CASE(30) SOLON_CASE(31) SOLON_CASE(32)
+#undef SOLON_CASE
+    default:
+      solon_set_error("solon_locate: no projection kernel for %d rows per block", rb);
+      return SOLON_E_INVAL;
+  }
   SOLON_HIP(hipGetLastError());
   hipLaunchKernelGGL(reduce_kernel, dim3(P), dim3(256), 0, st, plan->dev.partials, (int)ntiles, P, plan->dev.rho);
   SOLON_HIP(hipGetLastError());

@@ -130,11 +130,14 @@ def test_unaligned_rows_use_general_kernels():
 
 
 @pytest.mark.parametrize("grid", [3, 0])
-def test_phase_separated_encode(grid):
-    """The persistent, phase-separated encoder forced onto small inputs: with three blocks a group takes several
-    read / write phases and the last one is ragged; with the full grid most threads have nothing to do."""
+def test_phase_separated_kernels(grid):
+    """The persistent, phase-separated encoder and recombination forced onto small inputs: with three blocks the
+    work takes several read / write phases and the last one is ragged; with the full grid most threads have
+    nothing to do."""
     solon.solon_tune("encode_phase", 1)
     solon.solon_tune("encode_phase_grid", grid)
+    solon.solon_tune("decode_phase", 1)
+    solon.solon_tune("decode_phase_grid", grid)
     try:
         run_case(63, 3, 4, 131_075, seed=21)                                   # fp32, 11/10-node groups, tail chunk
         run_case(15, 1, 2, 40_002, seed=22)
@@ -149,10 +152,13 @@ def test_phase_separated_encode(grid):
     finally:
         solon.solon_tune("encode_phase", -1)
         solon.solon_tune("encode_phase_grid", 0)
+        solon.solon_tune("decode_phase", -1)
+        solon.solon_tune("decode_phase_grid", 0)
 
 
-def test_phase_separated_encode_equals_flat_kernel_bitwise():
-    """Both fast encoders add the gradients in batch order and evaluate the same Horner scheme: identical bits."""
+def test_phase_separated_kernels_equal_flat_kernels_bitwise():
+    """Both fast encoders add the gradients in batch order and evaluate the same Horner scheme, and both
+    recombination kernels accumulate the chosen rows in the same order: identical bits."""
     cfg = dict(P=63, d=3_000_000, dtype="f32", dist="normal", sigma=0.01)
     plan = solon.Plan(63, 3, 4, cfg["d"])
     G = workloads.make_gradients(cfg, DEV, 31, d=cfg["d"])
@@ -167,8 +173,23 @@ def test_phase_separated_encode_equals_flat_kernel_bitwise():
             solon.solon_encode(plan, G, Zb)
             torch.cuda.synchronize()
             assert torch.equal(Za, Zb)
+        f = workloads.make_projection(plan.d_c, DEV, 32)
+        R = workloads.apply_attack(Za.clone(), [3, 40, 62], "mix", 33)
+        V, _ = solon.solon_locate(plan, R, f)
+        assert V == [3, 40, 62]
+        ua = torch.zeros(cfg["d"], dtype=torch.float32, device=DEV)
+        ub = torch.zeros_like(ua)
+        solon.solon_tune("decode_phase", 0)
+        solon.solon_decode(plan, R, ua)
+        solon.solon_tune("decode_phase", 1)
+        for _ in range(3):
+            ub.zero_()
+            solon.solon_decode(plan, R, ub)
+            torch.cuda.synchronize()
+            assert torch.equal(ua, ub)
     finally:
         solon.solon_tune("encode_phase", -1)
+        solon.solon_tune("decode_phase", -1)
 
 
 def test_decode_with_host_supplied_set():
