@@ -169,8 +169,10 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
             }
             store_chunks<NC, true>(zrow + u * NC, z);
           }
+          // one store in flight per wave, so that HBM is handed the addresses close to the order they were issued in
+          // (measured: 0 to 1.5 % faster than with all of a wave's stores queued at once)
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
-        __syncthreads();  // the block finishes one node's row before the next (measured: 1 % faster than free-running waves)
       }
       solon_phase_align(sync, ++nbar, spin_limit);
     }
