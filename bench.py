@@ -283,7 +283,7 @@ def main():
         "config": {"workload": args.config, **{k: main_res[k] for k in ("P", "s", "m", "d", "d_c", "q", "r", "grad_dtype", "attack")}},
         "effective_GBps": main_res["effective_GBps"], "pct_of_peak": 100.0 * main_res["effective_GBps"] / PEAK_HBM_GBS,
         "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"], "located_ok": main_res["located_ok"],
-        "roofline": {"kernel": "encode_vec_kernel (solon_encode)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
+        "roofline": {"kernel": "encode_phase_kernel (solon_encode; the persistent phase-separated encoder serves this size)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic},
         "cpu_baseline": cpu,
         "also": [{k: r[k] for k in ("workload", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps", "located_ok")}
