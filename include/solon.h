@@ -93,6 +93,9 @@ int solon_default_points(int r_g, float* out);
  *   G   device, B rows x d elements of the plan's grad dtype, row stride ldg elements (ldg >= d)
  *   Z   device, P rows x d_c fp32, row stride ldz elements (ldz >= d_c); rows of idle nodes are not written
  * Coordinates c >= d of the last chunk count as zero.  Group sums and the Horner evaluation are fp32.
+ * Large inputs run on a persistent grid whose blocks align their read and write phases through counters in the
+ * plan's workspace: overlapping two solon_encode / solon_decode calls of ONE plan on different streams stays
+ * correct (every wait is bounded) but loses that alignment, i.e. runs slower.
  */
 int solon_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, void* hip_stream);
 
@@ -148,8 +151,11 @@ int solon_decode_majority(solon_plan* plan, const float* R, int64_t ldr, float* 
  * device: SOLON_OK, SOLON_E_DECODE or SOLON_E_NUMERIC. */
 int solon_decode_status(solon_plan* plan, void* hip_stream);
 
-/* Launch-shape knobs for measurements (process-wide): "encode_blocks", "encode_nt", "encode_unit_mult",
- * "encode_force_generic", "project_blocks", "decode_blocks".  Unknown keys are stored and ignored. */
+/* Launch-shape knobs for measurements and tests (process-wide): "encode_phase", "decode_phase" (-1 = choose by size,
+ * 0 = flat kernels, 1 = the persistent phase-separated kernels wherever they are legal), "encode_phase_grid",
+ * "decode_phase_grid" (cap on the persistent grid, 0 = none), "phase_spin_limit", "project_rows", "project_seg",
+ * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic".
+ * Unknown keys are stored and ignored. */
 int solon_tune(const char* key, int value);
 
 const char* solon_last_error(void); /* thread-local, valid until the next failing call on this thread */
