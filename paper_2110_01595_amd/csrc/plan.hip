@@ -52,12 +52,16 @@ int solon_resident_grid(const void* kernel, int threads) {
   auto it = cache.find(kernel);
   if (it != cache.end()) return it->second;
   int dev = 0, cus = 0, per_cu = 0;
+  hipFuncAttributes attr;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess) {
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess ||
+      hipFuncGetAttributes(&attr, kernel) != hipSuccess) {
     (void)hipGetLastError();
     return 0;
   }
-  const int grid = cus * per_cu;
+  // a kernel that spills to scratch memory may get fewer resident waves than the occupancy query promises, and a
+  // persistent grid that is not resident all at once only waits out its spin limits: such a build uses the flat kernels
+  const int grid = attr.localSizeBytes > 0 ? 0 : cus * per_cu;
   cache[kernel] = grid;
   return grid;
 }
