@@ -23,10 +23,24 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // row of its bunch and walks its strips with 16-byte loads, so f is loaded once per RB rows of R.  All RB loads of
 // a strip are issued back to back with no branch between them: a bunch with fewer rows re-reads its last row
 // (in bounds, served by the cache) and drops those sums.
-template <int RB, bool VEC>
+template <int RB, bool VEC, bool XCD_MAP>
 __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ R, int64_t ldr, const float* __restrict__ f,
-                                                       int64_t d_c, int P, int seg, double* __restrict__ partials) {
-  const int bunch = blockIdx.x, tile = blockIdx.y;
+                                                       int64_t d_c, int P, int seg, int nbunch, int ntiles, double* __restrict__ partials) {
+  // Block -> (tile, bunch).  Workgroups are handed to the eight XCDs round-robin, each with its own L2: block L runs
+  // on XCD L % 8 as that XCD's (L / 8)-th block.  Numbering the work so that consecutive blocks OF ONE XCD are the
+  // bunches of one tile lets all bunches of a tile find its piece of f in that XCD's L2.
+  int bunch, tile;
+  if (XCD_MAP) {
+    const int64_t total = (int64_t)nbunch * ntiles;
+    const int64_t per_xcd = (total + 7) / 8;
+    const int64_t v = (int64_t)(blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    if ((int64_t)(blockIdx.x >> 3) >= per_xcd || v >= total) return;
+    tile = (int)(v / nbunch);
+    bunch = (int)(v - (int64_t)tile * nbunch);
+  } else {
+    bunch = blockIdx.x % nbunch;
+    tile = blockIdx.x / nbunch;
+  }
   const int row0 = bunch * RB;
   const int nrows = min(RB, P - row0);
   const int tid = threadIdx.x;
@@ -99,33 +113,40 @@ __global__ __launch_bounds__(256) void reduce_kernel(const double* __restrict__ 
 }
 
 template <int RB>
-static void project_launch(bool vec, dim3 grid, hipStream_t st, const float* R, int64_t ldr, const float* f, int64_t d_c, int P, int seg,
-                           double* partials) {
-  if (vec) hipLaunchKernelGGL((project_kernel<RB, true>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, partials);
-  else hipLaunchKernelGGL((project_kernel<RB, false>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, partials);
+static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipStream_t st, const float* R, int64_t ldr, const float* f,
+                           int64_t d_c, int P, int seg, double* partials) {
+  const int64_t total = (int64_t)nbunch * ntiles;
+  const dim3 grid((unsigned)(xcd_map ? (total + 7) / 8 * 8 : total));
+#define SOLON_LAUNCH(V, X) hipLaunchKernelGGL((project_kernel<RB, V, X>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, nbunch, ntiles, partials)
+  if (vec && xcd_map) SOLON_LAUNCH(true, true);
+  else if (vec) SOLON_LAUNCH(true, false);
+  else if (xcd_map) SOLON_LAUNCH(false, true);
+  else SOLON_LAUNCH(false, false);
+#undef SOLON_LAUNCH
 }
 
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
   const int P = plan->P;
-  // rows per bunch: the fewest bunches of at most 21 rows (the most that leave four waves per SIMD resident; measured on
-  // P = 100: 20 rows 6.65 TB/s, 25 rows 5.9 TB/s), of equal size where P allows
-  const int rb_max = std::max(1, std::min(SOLON_PROJ_ROWS, solon_tuning("project_rows", 21)));
+  // rows per bunch: the fewest bunches of at most 16 rows, of equal size where P allows.  With the XCD-aware block
+  // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing (measured at P = 100:
+  // 16 rows 6.75 TB/s, 20 rows 6.67, 25 rows 5.7 - the last leaves too few resident waves).
+  const int rb_max = std::max(1, std::min(SOLON_PROJ_ROWS, solon_tuning("project_rows", 16)));
   const int nbunch0 = (P + rb_max - 1) / rb_max;
   const int rb = (P + nbunch0 - 1) / nbunch0;
   const int nbunch = (P + rb - 1) / rb;
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
   const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
   const int64_t strips = std::max<int64_t>(1, (work + 255) / 256);
-  // strips per tile: 4 to 16 (measured best: 16 once there are well over 6000 blocks, 4 for small inputs), and
+  // strips per tile: 4 to 32 (measured best: 32 once there are well over 6000 blocks, 4 for small inputs), and
   // enough to keep the partial-sum table within its allocation
   int64_t seg = solon_tuning("project_seg", 0);
-  if (seg <= 0) seg = std::min<int64_t>(16, std::max<int64_t>(4, strips * nbunch / 6000));
+  if (seg <= 0) seg = std::min<int64_t>(32, std::max<int64_t>(4, strips * nbunch / 6000));
   seg = std::max<int64_t>(seg, (strips + SOLON_PROJ_MAX_TILES - 1) / SOLON_PROJ_MAX_TILES);
   const int64_t ntiles = (strips + seg - 1) / seg;
   plan->proj_tiles = (int)ntiles;
-  dim3 grid((unsigned)nbunch, (unsigned)ntiles);
+  const bool xcd_map = solon_tuning("project_xcd_map", 1) != 0 && nbunch > 1;
   switch (rb) {
-#define SOLON_CASE(N) case N: project_launch<N>(vec, grid, st, R, ldr, f, plan->d_c, P, (int)seg, plan->dev.partials); break;
+#define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, plan->d_c, P, (int)seg, plan->dev.partials); break;
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
     SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
     SOLON_CASE(17) SOLON_CASE(18) SOLON_CASE(19) SOLON_CASE(20) SOLON_CASE(21) SOLON_CASE(22) SOLON_CASE(23) SOLON_CASE(24)
