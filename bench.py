@@ -3,7 +3,9 @@
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--also C4] [--no-cpu-baseline]
 
 A step is one pass of the whole path over one batch of synthetic gradients that are already resident in
-HBM: solon_encode (G -> Z), solon_locate (R, f -> V, psi tables) and solon_decode (R -> u) on one stream.
+HBM: solon_encode (G -> Z), then phi and psi (R, f -> V, u) on one stream - by default through solon_locate_decode,
+which does both in one pass over R; --two-pass times solon_locate and solon_decode as separate calls instead (the
+default run also reports those, from a few extra steps outside the timed region).
 R is the encoder's output with the configuration's Byzantine rows overwritten; that harness step runs once,
 before the timed region, into its own buffer, so each timed step moves exactly the method's bytes.
 Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).
@@ -32,7 +34,7 @@ def algorithmic_bytes(cfg, plan):
     return dict(encode=enc, locate=loc, decode=dec, total=enc + loc + dec)
 
 
-def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False):
+def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False, two_pass=False):
     import numpy as np
     import torch
 
@@ -60,16 +62,21 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
     torch.cuda.synchronize()
 
-    def step(events=None):
+    def step(events=None, one_pass=not two_pass):
         if events is not None:
             events[0].record()
         solon.solon_encode(plan, G, Z)
         if events is not None:
             events[1].record()
-        solon.solon_locate(plan, R, f, want_host=False)
-        if events is not None:
-            events[2].record()
-        solon.solon_decode(plan, R, u)
+        if one_pass:                                         # phi and psi in one pass over R
+            solon.solon_locate_decode(plan, R, f, u, want_host=False)
+            if events is not None:
+                events[2].record()
+        else:
+            solon.solon_locate(plan, R, f, want_host=False)
+            if events is not None:
+                events[2].record()
+            solon.solon_decode(plan, R, u)
         if events is not None:
             events[3].record()
 
@@ -89,15 +96,27 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     phase = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # ms
     enc_ms, loc_ms, dec_ms = phase.mean(axis=0).tolist()
     ab = algorithmic_bytes(cfg, plan)
+    if not two_pass:                                         # for the record: the two separate passes, a few steps
+        ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(max(3, steps // 4))]
+        step(one_pass=False)
+        for e in ev2:
+            step(e, one_pass=False)
+        torch.cuda.synchronize()
+        two = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev2]).mean(axis=0).tolist()
     res = dict(
         workload=name, P=P, s=s, m=m, d=d, d_c=d_c, q=plan.q, r=plan.r, grad_dtype=cfg["dtype"], attack=cfg["attack"],
         located_ok=(status == 0 and V == byz), ms_per_step=ms_step,
         coords_per_s=P * d / (ms_step * 1e-3),
         effective_GBps=ab["total"] / (ms_step * 1e-3) / 1e9,
-        phase_ms=dict(encode=enc_ms, locate=loc_ms, decode=dec_ms),
-        phase_GBps=dict(encode=ab["encode"] / enc_ms / 1e6, locate=ab["locate"] / loc_ms / 1e6, decode=ab["decode"] / dec_ms / 1e6),
         algorithmic_bytes=ab,
     )
+    if two_pass:
+        res["phase_ms"] = dict(encode=enc_ms, locate=loc_ms, decode=dec_ms)
+        res["phase_GBps"] = dict(encode=ab["encode"] / enc_ms / 1e6, locate=ab["locate"] / loc_ms / 1e6, decode=ab["decode"] / dec_ms / 1e6)
+    else:
+        res["phase_ms"] = dict(encode=enc_ms, locate_decode=loc_ms)
+        res["phase_GBps"] = dict(encode=ab["encode"] / enc_ms / 1e6, locate_decode=(ab["locate"] + ab["decode"]) / loc_ms / 1e6)
+        res["two_pass_phase_ms"] = dict(encode=two[0], locate=two[1], decode=two[2])
     if check_sum:   # Def. 1 of the paper over every coordinate: u against the fp64 column sum of G (torch, on the device)
         num = den = 0.0
         for c0 in range(0, d, 1 << 22):
@@ -227,6 +246,7 @@ def main():
     ap.add_argument("--config", default="C5")
     ap.add_argument("--also", default="C4", help="comma-separated further workloads reported inside the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-pass", action="store_true", help="time solon_locate + solon_decode instead of solon_locate_decode")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
                     help="launch-shape knob passed to solon_tune before the run (measurement aid; may be repeated)")
     ap.add_argument("--sweep", choices=["paper", "repetition"], default=None,
@@ -262,10 +282,10 @@ def main():
         sweep_repetition(args.steps, args.warmup)
         return
 
-    main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline)
+    main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline, two_pass=args.two_pass)
     others = []
     for name in [n for n in args.also.split(",") if n and n != args.config]:
-        r, _ = run_config(name, args.steps, args.warmup, False)
+        r, _ = run_config(name, args.steps, args.warmup, False, two_pass=args.two_pass)
         others.append(r)
 
     enc_bytes = main_res["algorithmic_bytes"]["encode"]
@@ -282,12 +302,13 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, **{k: main_res[k] for k in ("P", "s", "m", "d", "d_c", "q", "r", "grad_dtype", "attack")}},
         "effective_GBps": main_res["effective_GBps"], "pct_of_peak": 100.0 * main_res["effective_GBps"] / PEAK_HBM_GBS,
-        "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"], "located_ok": main_res["located_ok"],
+        "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"],
+        "two_pass_phase_ms": main_res.get("two_pass_phase_ms"), "located_ok": main_res["located_ok"],
         "roofline": {"kernel": "encode_phase_kernel (solon_encode; the persistent phase-separated encoder serves this size)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic},
         "cpu_baseline": cpu,
-        "also": [{k: r[k] for k in ("workload", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps", "located_ok")}
-                 for r in others],
+        "also": [{k: r[k] for k in ("workload", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps", "located_ok")
+                  + (() if args.two_pass else ("two_pass_phase_ms",))} for r in others],
     }
     print(json.dumps(line))
 

@@ -132,6 +132,22 @@ int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* b
                  void* hip_stream);
 
 /*
+ * solon_locate followed by solon_decode, in one pass over R (same paper passages; same V, same status, u to the same
+ * bar).  The rows for psi are guessed first - by the locator itself, run on the projection of a leading sample of the
+ * columns - and the single pass over R produces the exact projections of all P rows together with the recombination
+ * of the guessed rows.  The locator then runs on the exact projections as in solon_locate; only if one of the guessed
+ * rows turns out to be in V (possible only when a node corrupts nothing but columns outside the sample) the
+ * recombination is repeated with the right rows, decided on the device.  Reads R about once instead of
+ * 1 + q m / P times.  Falls back to the two separate passes for m other than 1, 2, 4, unaligned buffers, plans with
+ * idle nodes and small inputs.
+ *   R, f            device, as for solon_locate
+ *   u               device, d fp32, as for solon_decode
+ *   byz_idx, n_byz, rho_out   host or NULL, as for solon_locate; asynchronous when all three are NULL
+ */
+int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr, const float* f, float* u, int32_t* byz_idx,
+                        int32_t* n_byz, double* rho_out, void* hip_stream);
+
+/*
  * Repetition-code decoder for m = 1 (every honest node of a group sends the group's gradient sum itself; the
  * paper's appendix on the repetition code with its streaming majority vote): u[c] = sum over groups of the value
  * that more than half of the group's nodes sent for coordinate c.  Needs no projection vector and no locate call;
@@ -154,7 +170,9 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
 /* Launch-shape knobs for measurements and tests (process-wide): "encode_phase", "decode_phase" (-1 = choose by size,
  * 0 = flat kernels, 1 = the persistent phase-separated kernels wherever they are legal), "encode_phase_grid",
  * "decode_phase_grid" (cap on the persistent grid, 0 = none), "phase_spin_limit", "project_rows", "project_seg",
- * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic".
+ * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic",
+ * "fuse" (-1 = solon_locate_decode chooses by size, 0 = always two passes, 1 = one pass wherever legal), "fuse_grid",
+ * "fuse_sample" (columns of the sample projection behind the guess).
  * Unknown keys are stored and ignored. */
 int solon_tune(const char* key, int value);
 

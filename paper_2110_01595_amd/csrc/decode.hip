@@ -18,7 +18,8 @@ template <> struct chunk_vec<4> { typedef f32x4 type; };
 template <int M, int CH, bool VEC>
 __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ rows,
                                                          const float* __restrict__ coef, float* __restrict__ u, int64_t d,
-                                                         int64_t d_c, int64_t p_begin) {
+                                                         int64_t d_c, int64_t p_begin, const int32_t* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;  // a speculative recombination already produced u
   const int64_t nunits = (d_c + CH - 1) / CH;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t unit = p_begin / CH + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; unit < nunits; unit += stride) {
@@ -75,7 +76,9 @@ constexpr int recombine_phase_units(int m) { return m == 4 ? 8 : m == 2 ? 6 : 8;
 template <int M>
 __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* __restrict__ R, int64_t ldr, int q,
                                                                    const int32_t* __restrict__ rows, const float* __restrict__ coef,
-                                                                   float* __restrict__ u, int64_t nunits, uint32_t* sync, int spin_limit) {
+                                                                   float* __restrict__ u, int64_t nunits, uint32_t* sync, int spin_limit,
+                                                                   const int32_t* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;  // every block leaves before the first alignment point: the counters stay zero
   constexpr int CH = 4 / M;
   constexpr int U = recombine_phase_units(M);
   typedef typename chunk_vec<CH>::type vt;
@@ -140,7 +143,8 @@ __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* _
 template <int M>
 __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __restrict__ R, int64_t ldr, int q,
                                                               const int32_t* __restrict__ rows, const float* __restrict__ coef,
-                                                              float* __restrict__ u) {
+                                                              float* __restrict__ u, const int32_t* __restrict__ run_flag) {
+  if (run_flag && *run_flag == 0) return;
   __shared__ float tile_out[256 * M];
   const int tid = threadIdx.x;
   const int64_t tile = blockIdx.x;
@@ -165,7 +169,7 @@ __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __rest
 }
 
 template <int M, int CH = ((M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4))>  // CH * M is a multiple of four
-static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
+static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st) {
   // CH-float loads from the rows of R and 16-byte stores of u
   const bool vec = ((uintptr_t)R % (4 * CH) == 0) && (ldr % CH == 0) && ((uintptr_t)u % 16 == 0);
   const int cap = solon_tuning("decode_blocks", 1 << 22);
@@ -174,7 +178,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
     const int64_t ntiles = plan->d / (256 * M);  // tiles that lie entirely below d
     if (ntiles > 0 && (uintptr_t)u % 16 == 0 && solon_tuning("decode_force_generic", 0) == 0) {
       hipLaunchKernelGGL((recombine_tile_kernel<M>), dim3((unsigned)ntiles), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u);
+                         plan->dev.dec_coef, u, run_flag);
       SOLON_HIP(hipGetLastError());
       p_begin = ntiles * 256;
     }
@@ -194,7 +198,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
     }
     if (phase_grid > 0) {
       hipLaunchKernelGGL((recombine_phase_kernel<M>), dim3((unsigned)phase_grid), dim3(1024), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), run_flag);
       SOLON_HIP(hipGetLastError());
       p_begin = punits * PCH;  // a multiple of every CH used below
     }
@@ -205,22 +209,49 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
   blocks = std::max<int64_t>(blocks, 1);
   if (vec)
     hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag);
   else
     hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
 
-int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st) {
+template <int M, int CH = ((M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4))>
+static int recombine_from(const solon_plan* plan, const float* R, int64_t ldr, float* u, int64_t p_start, hipStream_t st) {
+  if (p_start >= plan->d_c) return SOLON_OK;
+  const bool vec = ((uintptr_t)R % (4 * CH) == 0) && (ldr % CH == 0) && ((uintptr_t)u % 16 == 0);
+  const int64_t nunits = (plan->d_c - p_start + CH - 1) / CH;
+  const int64_t blocks = std::max<int64_t>(1, (nunits + 255) / 256);
+  if (vec)
+    hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr);
+  else
+    hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr);
+  SOLON_HIP(hipGetLastError());
+  return SOLON_OK;
+}
+
+int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t ldr, float* u, int64_t p_start, hipStream_t st) {
+  switch (plan->m) {
+#define SOLON_CASE(MV) case MV: return recombine_from<MV>(plan, R, ldr, u, p_start, st);
+    SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
+    SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
+#undef SOLON_CASE
+  }
+  solon_set_error("solon_decode: no kernel for m = %d", plan->m);
+  return SOLON_E_INVAL;
+}
+
+int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st) {
   if (plan->m == 4) {  // chunks per thread: two measured best on C4 / C5 (0.68 vs 0.70 ms with one, 0.95 ms with four)
     const int ch = solon_tuning("decode_ch", 2);
-    if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, st);
-    if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, st);
+    if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, run_flag, st);
+    if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, run_flag, st);
   }
   switch (plan->m) {
-#define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, st);
+#define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, run_flag, st);
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
     SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
 #undef SOLON_CASE
@@ -271,11 +302,11 @@ extern "C" int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const
       }
     }
     SOLON_HIP(hipMemcpyAsync(plan->dev.vmask, h_vmask, sizeof(int32_t) * plan->P, hipMemcpyHostToDevice, st));
-    int rc = solon_launch_solve(plan, false, st);
+    int rc = solon_launch_solve(plan, SOLVE_TABLES, st);
     if (rc != SOLON_OK) return rc;
   } else if (byz_idx) {
     solon_set_error("solon_decode: n_byz < 0 requires a null index list");
     return SOLON_E_INVAL;
   }
-  return solon_launch_recombine(plan, R, ldr, u, st);
+  return solon_launch_recombine(plan, R, ldr, u, nullptr, st);
 }

@@ -125,7 +125,8 @@ static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipSt
 #undef SOLON_LAUNCH
 }
 
-int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
+int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles_out,
+                           hipStream_t st) {
   const int P = plan->P;
   // rows per bunch: the fewest bunches of at most 16 rows, of equal size where P allows.  With the XCD-aware block
   // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing (measured at P = 100:
@@ -135,18 +136,20 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
   const int rb = (P + nbunch0 - 1) / nbunch0;
   const int nbunch = (P + rb - 1) / rb;
   const bool vec = ((uintptr_t)R % 16 == 0) && (ldr % 4 == 0) && ((uintptr_t)f % 16 == 0);
-  const int64_t work = vec ? plan->d_c / 4 : plan->d_c;
+  const int64_t work = vec ? ncols / 4 : ncols;
   const int64_t strips = std::max<int64_t>(1, (work + 255) / 256);
   // strips per tile: 4 to 32 (measured best: 32 once there are well over 6000 blocks, 4 for small inputs), and
   // enough to keep the partial-sum table within its allocation
+  const int64_t room = SOLON_PROJ_MAX_TILES - tile_base;
   int64_t seg = solon_tuning("project_seg", 0);
   if (seg <= 0) seg = std::min<int64_t>(32, std::max<int64_t>(4, strips * nbunch / 6000));
-  seg = std::max<int64_t>(seg, (strips + SOLON_PROJ_MAX_TILES - 1) / SOLON_PROJ_MAX_TILES);
+  seg = std::max<int64_t>(seg, (strips + room - 1) / room);
   const int64_t ntiles = (strips + seg - 1) / seg;
-  plan->proj_tiles = (int)ntiles;
+  *ntiles_out = (int)ntiles;
   const bool xcd_map = solon_tuning("project_xcd_map", 1) != 0 && nbunch > 1;
+  double* partials = plan->dev.partials + (int64_t)tile_base * P;
   switch (rb) {
-#define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, plan->d_c, P, (int)seg, plan->dev.partials); break;
+#define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, ncols, P, (int)seg, partials); break;
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
     SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
     SOLON_CASE(17) SOLON_CASE(18) SOLON_CASE(19) SOLON_CASE(20) SOLON_CASE(21) SOLON_CASE(22) SOLON_CASE(23) SOLON_CASE(24)
@@ -157,9 +160,21 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
       return SOLON_E_INVAL;
   }
   SOLON_HIP(hipGetLastError());
-  hipLaunchKernelGGL(reduce_kernel, dim3(P), dim3(256), 0, st, plan->dev.partials, (int)ntiles, P, plan->dev.rho);
+  return SOLON_OK;
+}
+
+int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st) {
+  plan->proj_tiles = ntiles;
+  hipLaunchKernelGGL(reduce_kernel, dim3(plan->P), dim3(256), 0, st, plan->dev.partials, ntiles, plan->P, plan->dev.rho);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
+}
+
+int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
+  int ntiles = 0;
+  const int rc = solon_project_partials(plan, R, ldr, f, plan->d_c, 0, &ntiles, st);
+  if (rc != SOLON_OK) return rc;
+  return solon_project_reduce(plan, ntiles, st);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -288,8 +303,13 @@ __device__ double wave_polyfit(double x, double y, bool use, int m) {
   return fit;
 }
 
+// mode: SOLVE_TABLES = psi's tables for the located set already in vmask; SOLVE_LOCATE = phi, then psi's tables;
+// SOLVE_SPECULATE = phi on a projection of a sample of the columns, as a guess of the located set for the fused
+// locate + decode pass: never fails (a group it cannot explain is taken as clean) and leaves vmask and status alone.
 struct solve_args {
-  int s, m, run_locator;
+  int s, m, mode;
+  const int32_t* guess_rows;  // SOLVE_LOCATE: rows a speculative recombination used, or null
+  int32_t* redo;              // set to 1 when some group's rows differ from guess_rows; SOLVE_SPECULATE clears it
   const int32_t* grp_off;
   const int32_t* grp_nodes;
   const float* w;
@@ -310,8 +330,9 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   const double wi = in_group ? (double)a.w[node] : 0.0;
   int st = SOLON_OK;
   bool located = false;
+  if (a.mode == SOLVE_SPECULATE && g == 0 && lane == 0) *a.redo = 0;
 
-  if (a.run_locator) {
+  if (a.mode != SOLVE_TABLES) {
     const double rho = in_group ? a.rho[node] : 0.0;
     const bool finite = in_group && isfinite(rho);
     const unsigned long long fin_mask = __ballot(finite);
@@ -397,7 +418,14 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
         if (finite && ((flag_mask >> pos) & 1ull)) located = true;
       }
     }
-    if (in_group) a.vmask[node] = located ? 1 : 0;
+    if (a.mode == SOLVE_SPECULATE) {
+      if (st != SOLON_OK) {  // the sample cannot be explained: guess that the group is clean
+        st = SOLON_OK;
+        located = false;
+      }
+    } else if (in_group) {
+      a.vmask[node] = located ? 1 : 0;
+    }
   } else {
     located = in_group && a.vmask[node] != 0;
   }
@@ -430,6 +458,10 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
       S.val[tpos] = wi;
       a.dec_rows[g * m + tpos] = node;
     }
+    if (a.mode == SOLVE_LOCATE && a.guess_rows) {  // same rows in the same order give the same table
+      const bool differs = taken && a.guess_rows[g * m + tpos] != node;
+      if (__ballot(differs) && lane == 0) *a.redo = 1;
+    }
     __syncthreads();
     if (taken) {
       double* poly = S.lag[tpos];
@@ -459,14 +491,22 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
     const unsigned long long bad = __ballot(lane < m && !(rowsum <= SOLON_INV_NORM_MAX));
     if (bad) st = SOLON_E_NUMERIC;
   }
-  if (lane == 0) a.status[g] = st;
+  if (a.mode == SOLVE_LOCATE && a.guess_rows && st != SOLON_OK && lane == 0) *a.redo = 1;
+  if (lane == 0 && a.mode != SOLVE_SPECULATE) a.status[g] = st;
 }
 
-int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st) {
+int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st) {
   solve_args a;
-  a.s = plan->s; a.m = plan->m; a.run_locator = run_locator ? 1 : 0;
+  a.s = plan->s; a.m = plan->m; a.mode = mode;
   a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
-  a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
+  a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.redo = plan->dev.redo;
+  a.guess_rows = nullptr;
+  a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
+  if (mode == SOLVE_SPECULATE) {
+    a.dec_rows = plan->dev.spec_rows; a.dec_coef = plan->dev.spec_coef;
+  } else if (mode == SOLVE_LOCATE_CHECK) {
+    a.mode = SOLVE_LOCATE; a.guess_rows = plan->dev.spec_rows;
+  }
   hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
@@ -512,7 +552,7 @@ extern "C" int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const
   hipStream_t st = (hipStream_t)hip_stream;
   int rc = solon_launch_project(plan, R, ldr, f, st);
   if (rc != SOLON_OK) return rc;
-  rc = solon_launch_solve(plan, true, st);
+  rc = solon_launch_solve(plan, SOLVE_LOCATE, st);
   if (rc != SOLON_OK) return rc;
   if (!byz_idx && !n_byz && !rho_out) return SOLON_OK;
   std::vector<int32_t> vm(plan->P);

@@ -236,6 +236,9 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   const size_t o_rows = take(sizeof(int32_t) * q * m);
   const size_t o_coef = take(sizeof(float) * q * m * m);
   const size_t o_sync = take(sizeof(uint32_t) * SOLON_SYNC_WORDS);
+  const size_t o_srows = take(sizeof(int32_t) * q * m);
+  const size_t o_scoef = take(sizeof(float) * q * m * m);
+  const size_t o_redo = take(sizeof(int32_t));
   p->ws_bytes = off;
   hipError_t e = hipMalloc(&p->ws, p->ws_bytes);
   if (e != hipSuccess) {
@@ -255,6 +258,9 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->dev.dec_rows = (int32_t*)(base + o_rows);
   p->dev.dec_coef = (float*)(base + o_coef);
   p->dev.grid_sync = (uint32_t*)(base + o_sync);
+  p->dev.spec_rows = (int32_t*)(base + o_srows);
+  p->dev.spec_coef = (float*)(base + o_scoef);
+  p->dev.redo = (int32_t*)(base + o_redo);
   p->pinned_bytes = align_up(sizeof(double) * P + sizeof(int32_t) * (P + q), 256);
   e = hipHostMalloc(&p->pinned, p->pinned_bytes, hipHostMallocDefault);
   if (e != hipSuccess) {

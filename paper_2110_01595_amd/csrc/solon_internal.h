@@ -27,6 +27,9 @@ struct solon_dev {
   int32_t* dec_rows;     // [q * m] rows of R chosen for psi
   float* dec_coef;       // [q][m][m] psi's coefficients T[g][l][t], stored as [g][t][l]
   uint32_t* grid_sync;   // [SOLON_SYNC_WORDS] arrival counters of the phase-separated kernels; zero between launches
+  int32_t* spec_rows;    // [q * m] rows guessed for psi by the fused locate + decode pass
+  float* spec_coef;      // [q][m][m] their coefficient table
+  int32_t* redo;         // [1] 1 = the guess was wrong, the recombination has to run again
 };
 
 struct solon_plan {
@@ -61,7 +64,19 @@ int solon_resident_grid(const void* kernel, int threads);
 // launchers (defined next to their kernels)
 int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st);
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st);
-int solon_launch_solve(solon_plan* plan, bool run_locator, hipStream_t st);
+// the two halves of solon_launch_project: per-tile partial projections of columns [0, ncols) of R and f, written to tiles
+// tile_base, tile_base + 1, ... of the plan's table (*ntiles receives how many); and the fixed-order sum of the first
+// ntiles tiles into rho
+int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles, hipStream_t st);
+int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st);
+// modes of the per-group solve wavefront: psi's tables for the located set already on the device; phi, then psi's
+// tables; phi on a projection of a sample of the columns as a guess for the fused locate + decode pass (never fails,
+// writes the guess tables only); phi that also raises the redo flag when its rows differ from the guess
+enum { SOLVE_TABLES = 0, SOLVE_LOCATE = 1, SOLVE_SPECULATE = 2, SOLVE_LOCATE_CHECK = 3 };
+int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st);
 // waits for the stream, copies status (and optionally the located mask and rho) to the host, returns the worst group status
 int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host, double* rho_host);
-int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, hipStream_t st);
+// run_flag: device int32 or null; when it points at 0 the kernels return at once (u already holds the result)
+int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st);
+// chunks p_start .. d_c - 1 only (p_start a multiple of four), with the general kernel
+int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t ldr, float* u, int64_t p_start, hipStream_t st);

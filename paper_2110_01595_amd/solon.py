@@ -18,7 +18,8 @@ SOLON_Q_GROUPS, SOLON_Q_REDUNDANCY, SOLON_Q_MESSAGE_LEN, SOLON_Q_MAX_GROUP, SOLO
 
 EXPORTS = [
     "solon_plan_create", "solon_plan_destroy", "solon_plan_query", "solon_plan_groups", "solon_plan_points",
-    "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_decode_majority", "solon_decode_status",
+    "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_locate_decode", "solon_decode_majority",
+    "solon_decode_status",
     "solon_tune",
     "solon_last_error",
 ]
@@ -62,6 +63,8 @@ def lib():
     L.solon_locate.restype = i32
     L.solon_decode.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.solon_decode.restype = i32
+    L.solon_locate_decode.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    L.solon_locate_decode.restype = i32
     L.solon_decode_majority.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.solon_decode_majority.restype = i32
     L.solon_decode_status.argtypes = [vp, vp]
@@ -177,6 +180,20 @@ def solon_decode(plan, R, u, byz=None, stream=None):
     else:
         idx = np.ascontiguousarray(byz, dtype=np.int32)
         _check(lib().solon_decode(plan._h, _dev_ptr(R), R.stride(0), _np_ptr(idx), len(idx), _dev_ptr(u), _stream(stream)))
+
+
+def solon_locate_decode(plan, R, f, u, want_host=True, want_rho=False, stream=None):
+    """solon_locate + solon_decode in one pass over R.  Returns (located list or None, rho or None)."""
+    assert R.is_cuda and f.is_cuda and u.is_cuda and R.stride(1) == 1 and f.is_contiguous() and u.is_contiguous()
+    if not want_host and not want_rho:
+        _check(lib().solon_locate_decode(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(f), _dev_ptr(u), None, None, None, _stream(stream)))
+        return None, None
+    idx = np.full(max(1, plan.q * plan.s), -1, dtype=np.int32)
+    n = ctypes.c_int32(0)
+    rho = np.empty(plan.P, dtype=np.float64) if want_rho else None
+    _check(lib().solon_locate_decode(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(f), _dev_ptr(u), _np_ptr(idx), ctypes.byref(n),
+                                     _np_ptr(rho), _stream(stream)))
+    return idx[: n.value].tolist(), rho
 
 
 def solon_decode_majority(plan, R, u, want_host=True, stream=None):

@@ -88,6 +88,14 @@ def test_full_size_config(name, u_tol):
     say("  located", V, "planted", byz, round(time.time() - t_start, 1), "s")
     assert V == byz
 
+    # the one-pass entry point (what bench.py times): same located set, same projections, same bits of u
+    u1 = torch.empty(d, dtype=torch.float32, device=DEV)
+    V1, rho1 = solon.solon_locate_decode(plan, R, f, u1, want_rho=True)
+    assert solon.solon_decode_status(plan) == solon.SOLON_OK
+    assert V1 == V and np.allclose(rho1, rho, rtol=1e-12, atol=0)
+    assert torch.equal(u1, u)
+    del u1
+
     # projection and located set: the oracle streams all of R
     rho_ref = np.zeros(P)
     mag = np.zeros(P)

@@ -22,7 +22,8 @@ def host(t):
 
 
 def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, seed=0, dist="normal", sigma=0.01,
-             check_bruteforce=False, u_tol=1e-4, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False):
+             check_bruteforce=False, u_tol=1e-4, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False,
+             fused=False, attack_from_column=0):
     """One encode -> attack -> locate -> decode round, compared step by step with the oracle."""
     say("case", dict(P=P, s=s, m=m, d=d, dtype=dtype, attack=attack, byz=byz, seed=seed, pad=pad))
     cfg = dict(P=(P if B is None else B), d=d, dtype=dtype, dist=dist, sigma=sigma, mu_sigma=0.03)
@@ -54,8 +55,14 @@ def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, see
         byz = workloads.pick_byzantine(P, s if n_byz is None else n_byz, 200 + seed, within=active.tolist())
     R = Zfull.clone()[:, :d_c] if pad else Z.clone()
     workloads.apply_attack(R, byz, attack, 300 + seed)
+    if attack_from_column:  # the adversaries leave the leading columns alone
+        R[:, :attack_from_column] = Z[:, :attack_from_column]
     f = workloads.make_projection(d_c, DEV, 400 + seed)
-    V, rho = solon.solon_locate(plan, R, f, want_rho=True)
+    u = torch.full((d + 3,), 5.0, dtype=torch.float32, device=DEV)
+    if fused:
+        V, rho = solon.solon_locate_decode(plan, R, f, u[:d], want_rho=True)
+    else:
+        V, rho = solon.solon_locate(plan, R, f, want_rho=True)
     Rh, fh = R.cpu().numpy(), f.cpu().numpy()
     rho_ref = so.project(Rh, fh)
     fin = np.isfinite(rho_ref)
@@ -68,8 +75,8 @@ def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, see
     if check_bruteforce:
         assert so.locate(oplan, rho_ref, "bruteforce") == V
 
-    u = torch.full((d + 3,), 5.0, dtype=torch.float32, device=DEV)
-    solon.solon_decode(plan, R, u[:d], byz=V if decode_from_host else None)
+    if not fused:
+        solon.solon_decode(plan, R, u[:d], byz=V if decode_from_host else None)
     assert solon.solon_decode_status(plan) == solon.SOLON_OK
     torch.cuda.synchronize()
     assert bool((u[d:] == 5.0).all())
@@ -190,6 +197,71 @@ def test_phase_separated_kernels_equal_flat_kernels_bitwise():
     finally:
         solon.solon_tune("encode_phase", -1)
         solon.solon_tune("decode_phase", -1)
+
+
+@pytest.mark.parametrize("grid", [2, 0])
+def test_locate_decode_in_one_pass(grid):
+    """solon_locate_decode forced onto small inputs (two blocks: several ragged phases): same located set, same
+    projections, same u as the two separate calls, whether the guess from the sample columns holds or not."""
+    solon.solon_tune("fuse", 1)
+    solon.solon_tune("fuse_grid", grid)
+    solon.solon_tune("fuse_sample", 256)
+    try:
+        run_case(63, 3, 4, 131_075, seed=41, fused=True)                          # d not a multiple of 4 m: trailing columns
+        run_case(63, 3, 4, 131_072, attack="mix", seed=42, fused=True)
+        run_case(100, 5, 4, 200_000, attack="mix", seed=43, fused=True)
+        run_case(100, 5, 4, 65_536, attack="noise100", n_byz=0, seed=44, fused=True)                      # nobody misbehaves
+        run_case(100, 5, 4, 100_000, attack="noise100", seed=45, fused=True, attack_from_column=4096)     # invisible in the sample
+        run_case(63, 3, 4, 100_000, attack="flip10", seed=46, fused=True, attack_from_column=300)
+        run_case(15, 1, 2, 40_002, seed=47, fused=True)
+        run_case(31, 2, 2, 50_000, attack="alie", dist="shared_mean", seed=48, fused=True)
+        run_case(7, 1, 1, 70_001, seed=49, fused=True)
+        run_case(63, 3, 4, 24_000, attack="nan", seed=50, fused=True)
+        run_case(63, 3, 4, 24_000, attack="inf", seed=51, fused=True)
+        run_case(100, 5, 4, 24_000, attack="huge", seed=52, fused=True)
+        oplan = so.make_plan(63, 3, 4)
+        run_case(63, 3, 4, 50_000, attack="mix", byz=oplan.nodes[2][:3].tolist(), seed=53, fused=True)    # all in one group
+        run_case(20, 2, 5, 25_003, seed=54, fused=True)                           # m = 5: falls back to the two passes
+        run_case(15, 1, 2, 40_002, pad=1, seed=55, fused=True)                    # unaligned rows: falls back
+    finally:
+        solon.solon_tune("fuse", -1)
+        solon.solon_tune("fuse_grid", 0)
+        solon.solon_tune("fuse_sample", 1 << 19)
+
+
+def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
+    cfg = dict(P=63, d=2_000_000, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(63, 3, 4, cfg["d"])
+    G = workloads.make_gradients(cfg, DEV, 61, d=cfg["d"])
+    Z = torch.zeros((63, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    f = workloads.make_projection(plan.d_c, DEV, 62)
+    ua = torch.zeros(cfg["d"], dtype=torch.float32, device=DEV)
+    ub = torch.zeros_like(ua)
+    try:
+        solon.solon_tune("fuse", 1)
+        solon.solon_tune("fuse_sample", 1024)
+        for byz, from_col in (([], 0), ([3, 40, 62], 0), ([3, 40, 62], 2048), ([0, 1, 2], 5000)):
+            R = workloads.apply_attack(Z.clone(), byz, "mix", 63)
+            if from_col:
+                R[:, :from_col] = Z[:, :from_col]
+            Va, rho_a = solon.solon_locate(plan, R, f, want_rho=True)
+            solon.solon_decode(plan, R, ua)
+            for _ in range(2):
+                ub.zero_()
+                Vb, rho_b = solon.solon_locate_decode(plan, R, f, ub, want_rho=True)
+                torch.cuda.synchronize()
+                assert Va == Vb == sorted(byz)
+                assert np.allclose(rho_a, rho_b, rtol=1e-12, atol=0)
+                assert torch.equal(ua, ub), (byz, from_col)
+        # more than s corrupted nodes in one group: reported, as by solon_locate
+        R = workloads.apply_attack(Z.clone(), [0, 1, 2, 3], "noise100", 64)
+        with pytest.raises(solon.SolonError) as e:
+            solon.solon_locate_decode(plan, R, f, ub)
+        assert e.value.code == solon.SOLON_E_DECODE
+    finally:
+        solon.solon_tune("fuse", -1)
+        solon.solon_tune("fuse_sample", 1 << 19)
 
 
 def test_decode_with_host_supplied_set():
