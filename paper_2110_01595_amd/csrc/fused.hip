@@ -35,8 +35,7 @@ struct fuse_args {
   int64_t nunits;  // float4 column units: columns [0, 4 nunits), all of whose chunks lie below d
   int P, q;
   const int32_t* grp_off;
-  const int32_t* grp_nodes;
-  const int32_t* rows;  // guessed rows, [q][m]
+  const int32_t* order;  // every group's nodes, the guessed rows first
   const float* coef;    // their table, [q][m][m]
   double* partials;     // [pass * gridDim.x + block][P]
   float* u;
@@ -67,7 +66,7 @@ __device__ __forceinline__ double wave_sum_lane63(double v) {
 }
 
 // rows of R loaded back to back: as many as leave four waves per SIMD resident without spills
-constexpr int fuse_rows(int m) { return m == 4 ? 7 : 8; }
+constexpr int fuse_rows(int m) { return m == 4 ? 6 : 8; }
 
 // Dynamic LDS: one fp64 slot per (wavefront, node).  A wavefront parks the sums of its own columns there row by row,
 // so the loop over the groups needs no block-wide synchronisation (wavefronts that run in lockstep leave HBM idle while they
@@ -103,11 +102,14 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
     }
     for (int g = 0; g < a.q; ++g) {
       const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
-      int srow[M];  // the group's guessed rows, ascending like the group's node list
+      float cf[M][M];  // the guessed rows' table, held in scalar registers (wave-uniform)
 #pragma unroll
-      for (int t = 0; t < M; ++t) srow[t] = a.rows[g * M + t];
+      for (int t = 0; t < M; ++t)
+#pragma unroll
+        for (int l = 0; l < M; ++l)
+          cf[t][l] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a.coef[(g * M + t) * M + l])));
       const int nbatch = (n1 - n0 + FUSE_ROWS - 1) / FUSE_ROWS;
-      const int per_batch = (n1 - n0 + nbatch - 1) / nbatch;  // batches of equal size, at most FUSE_ROWS rows
+      const int per_batch = (n1 - n0 + nbatch - 1) / nbatch;  // batches of equal size, at most FUSE_ROWS rows, at least M
       for (int b0 = n0; b0 < n1; b0 += per_batch) {
         const int nb = min(per_batch, n1 - b0);
         double acc[FUSE_ROWS];
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
 #pragma unroll
         for (int r = 0; r < FUSE_ROWS; ++r) {
           acc[r] = 0.0;
-          node[r] = a.grp_nodes[b0 + min(r, nb - 1)];  // a short batch re-reads its last row
+          node[r] = __builtin_amdgcn_readfirstlane(a.order[b0 + min(r, nb - 1)]);  // wave-uniform; a short batch re-reads its last row
         }
 #pragma unroll
         for (int i = 0; i < FUSE_U; ++i) {
@@ -131,23 +133,17 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
             acc[r] = fma(f2, (double)rv[r].z, acc[r]);
             acc[r] = fma(f3, (double)rv[r].w, acc[r]);
           }
+          if (b0 == n0) {  // the group's first batch starts with the M guessed rows: their recombination
 #pragma unroll
-          for (int r = 0; r < FUSE_ROWS; ++r) {  // recombination of the guessed rows among them (wave-uniform tests)
-            if (r < nb) {
+            for (int t = 0; t < M; ++t) {
+              const float v[4] = {rv[t].x, rv[t].y, rv[t].z, rv[t].w};
 #pragma unroll
-              for (int t = 0; t < M; ++t) {
-                if (node[r] == srow[t]) {
-                  const float v[4] = {rv[r].x, rv[r].y, rv[r].z, rv[r].w};
+              for (int l = 0; l < M; ++l)
 #pragma unroll
-                  for (int l = 0; l < M; ++l) {
-                    const float cf = a.coef[(g * M + t) * M + l];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) out[i][c * M + l] = fmaf(cf, v[c], out[i][c * M + l]);
-                  }
-                }
-              }
+                for (int c = 0; c < 4; ++c) out[i][c * M + l] = fmaf(cf[t][l], v[c], out[i][c * M + l]);
             }
           }
+          __builtin_amdgcn_sched_barrier(0);  // one unit's rows in registers at a time: hoisting the next unit's loads spills
         }
 #pragma unroll
         for (int r = 0; r < FUSE_ROWS; ++r) {  // this wavefront's share of rho
@@ -249,8 +245,7 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
     // 2. one pass over R: exact projections of all rows, recombination of the guessed rows
     fuse_args a;
     a.R = R; a.ldr = ldr; a.f = f; a.nunits = nunits; a.P = P; a.q = plan->q;
-    a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes;
-    a.rows = plan->dev.spec_rows; a.coef = plan->dev.spec_coef;
+    a.grp_off = plan->dev.grp_off; a.order = plan->dev.spec_order; a.coef = plan->dev.spec_coef;
     a.partials = plan->dev.partials; a.u = u; a.sync = plan->dev.grid_sync;
     a.spin_limit = solon_tuning("fuse_spin_limit", 0);
     rc = m == 1 ? fused_pass<1>(plan, a, grid, st) : m == 2 ? fused_pass<2>(plan, a, grid, st) : fused_pass<4>(plan, a, grid, st);

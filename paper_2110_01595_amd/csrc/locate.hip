@@ -310,6 +310,7 @@ struct solve_args {
   int s, m, mode;
   const int32_t* guess_rows;  // SOLVE_LOCATE: rows a speculative recombination used, or null
   int32_t* redo;              // set to 1 when some group's rows differ from guess_rows; SOLVE_SPECULATE clears it
+  int32_t* order;             // SOLVE_SPECULATE: every group's nodes, the chosen rows first
   const int32_t* grp_off;
   const int32_t* grp_nodes;
   const float* w;
@@ -458,6 +459,10 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
       S.val[tpos] = wi;
       a.dec_rows[g * m + tpos] = node;
     }
+    if (a.mode == SOLVE_SPECULATE && in_group) {  // node order for the fused pass: chosen rows first, then the others
+      const unsigned long long rest = __ballot(in_group && !taken);
+      a.order[n0 + (taken ? tpos : m + __popcll(rest & ((1ull << lane) - 1ull)))] = node;
+    }
     if (a.mode == SOLVE_LOCATE && a.guess_rows) {  // same rows in the same order give the same table
       const bool differs = taken && a.guess_rows[g * m + tpos] != node;
       if (__ballot(differs) && lane == 0) *a.redo = 1;
@@ -501,6 +506,7 @@ int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st) {
   a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
   a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.redo = plan->dev.redo;
   a.guess_rows = nullptr;
+  a.order = plan->dev.spec_order;
   a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
   if (mode == SOLVE_SPECULATE) {
     a.dec_rows = plan->dev.spec_rows; a.dec_coef = plan->dev.spec_coef;

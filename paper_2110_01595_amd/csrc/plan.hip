@@ -239,6 +239,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   const size_t o_srows = take(sizeof(int32_t) * q * m);
   const size_t o_scoef = take(sizeof(float) * q * m * m);
   const size_t o_redo = take(sizeof(int32_t));
+  const size_t o_sorder = take(sizeof(int32_t) * std::max(1, p->n_active));
   p->ws_bytes = off;
   hipError_t e = hipMalloc(&p->ws, p->ws_bytes);
   if (e != hipSuccess) {
@@ -261,6 +262,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->dev.spec_rows = (int32_t*)(base + o_srows);
   p->dev.spec_coef = (float*)(base + o_scoef);
   p->dev.redo = (int32_t*)(base + o_redo);
+  p->dev.spec_order = (int32_t*)(base + o_sorder);
   p->pinned_bytes = align_up(sizeof(double) * P + sizeof(int32_t) * (P + q), 256);
   e = hipHostMalloc(&p->pinned, p->pinned_bytes, hipHostMallocDefault);
   if (e != hipSuccess) {

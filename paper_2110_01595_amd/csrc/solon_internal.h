@@ -29,6 +29,7 @@ struct solon_dev {
   uint32_t* grid_sync;   // [SOLON_SYNC_WORDS] arrival counters of the phase-separated kernels; zero between launches
   int32_t* spec_rows;    // [q * m] rows guessed for psi by the fused locate + decode pass
   float* spec_coef;      // [q][m][m] their coefficient table
+  int32_t* spec_order;   // [n_active] every group's nodes with the guessed rows first (both parts ascending)
   int32_t* redo;         // [1] 1 = the guess was wrong, the recombination has to run again
 };
 
