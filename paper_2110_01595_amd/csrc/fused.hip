@@ -26,7 +26,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define FUSE_U 2      // float4 column units per thread and phase
 #define FUSE_BLOCK 1024
-#define FUSE_SAMPLE (1 << 19)  // columns of the sample projection behind the guess
+#define FUSE_SAMPLE (1 << 17)  // columns of the sample projection behind the guess
 
 struct fuse_args {
   const float* R;

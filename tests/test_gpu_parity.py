@@ -226,7 +226,7 @@ def test_locate_decode_in_one_pass(grid):
     finally:
         solon.solon_tune("fuse", -1)
         solon.solon_tune("fuse_grid", 0)
-        solon.solon_tune("fuse_sample", 1 << 19)
+        solon.solon_tune("fuse_sample", 1 << 17)
 
 
 def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
@@ -261,7 +261,7 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
         assert e.value.code == solon.SOLON_E_DECODE
     finally:
         solon.solon_tune("fuse", -1)
-        solon.solon_tune("fuse_sample", 1 << 19)
+        solon.solon_tune("fuse_sample", 1 << 17)
 
 
 def test_decode_with_host_supplied_set():
