@@ -10,7 +10,7 @@
 
 #define SOLON_MAX_M 16          // largest compression ratio with a compiled kernel
 #define SOLON_PROJ_ROWS 32      // most rows of R one projection block accumulates at once
-#define SOLON_PROJ_MAX_TILES 8192
+#define SOLON_PROJ_MAX_TILES 16384
 #define SOLON_SYNC_WORDS 512     // 8 counters 128 bytes apart, one grid-wide counter, one exit counter
 
 // Device-side tables of a plan; every pointer points into the plan's single workspace allocation.
