@@ -120,6 +120,9 @@ template <typename T> struct phase_units;
 template <> struct phase_units<float> { static constexpr int U = 6; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
 
+// block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within 32 registers
+constexpr int tile_phase_tiles(int sums_per_tile) { return 32 / sums_per_tile > 0 ? 32 / sums_per_tile : 1; }
+
 template <int M, typename T>
 __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit) {
   constexpr int LV = load_traits<T>::LV;
@@ -173,6 +176,89 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
           // (measured: 0 to 1.5 % faster than with all of a wave's stores queued at once)
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
+      }
+      solon_phase_align(sync, ++nbar, spin_limit);
+    }
+  }
+  solon_phase_exit(sync);
+}
+
+// Phase-separated version of the tiled path (compression ratios that do not divide the load width), for large
+// inputs.  A persistent grid of 1024-thread blocks; a block-tile is 1024 consecutive chunks (1024 m coordinates) of
+// one group.  Read phase: every thread sums its share of UT block-tiles position-wise over the group's rows into
+// registers (coalesced 16-byte loads).  Write phase: tile by tile the sums pass through LDS, each thread picks up
+// the m coefficients of its own chunk and writes one message element per node.  Same order of additions as
+// encode_tile_kernel.
+template <int M, typename T>
+__global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, int64_t ntiles, int q, uint32_t* sync, int spin_limit) {
+  constexpr int LV = load_traits<T>::LV;
+  constexpr int NVEC = 1024 * M / LV;           // 16-byte vectors per row and block-tile (1024 m is a multiple of LV)
+  constexpr int NI = (NVEC + 1023) / 1024;      // vectors per thread and block-tile
+  constexpr int UT = tile_phase_tiles(NI * LV); // block-tiles per block and phase
+  extern __shared__ float ybar[];               // [1024 * M]
+  const int tid = threadIdx.x;
+  const int64_t per_phase = (int64_t)gridDim.x * UT;
+  const int nphase = (int)((ntiles + per_phase - 1) / per_phase);
+  uint32_t nbar = 0;
+  for (int g = 0; g < q; ++g) {
+    const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+    const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+    for (int ph = 0; ph < nphase; ++ph) {
+      // tile j of this block in this phase: consecutive blocks take consecutive tiles
+      const int64_t t0 = (int64_t)ph * per_phase + blockIdx.x;
+      float acc[UT][NI][LV];
+#pragma unroll
+      for (int j = 0; j < UT; ++j)
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+          for (int e = 0; e < LV; ++e) acc[j][i][e] = 0.0f;
+      for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+        const T* row = static_cast<const T*>(a.G) + (int64_t)a.grp_batches[k] * a.ldg;
+#pragma unroll
+        for (int j = 0; j < UT; ++j) {
+          int64_t tile = t0 + (int64_t)j * gridDim.x;
+          tile = tile < ntiles ? tile : ntiles - 1;  // past the end: the last tile again (in bounds, result unused)
+          const T* src = row + tile * (1024 * M);
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            int v = tid + 1024 * i;
+            if (NVEC % 1024 != 0) v = v < NVEC ? v : NVEC - 1;  // the tile's last vector again (unused)
+            load_add<true>(src + v * LV, acc[j][i]);
+          }
+        }
+      }
+      solon_phase_align(sync, ++nbar, spin_limit);
+#pragma unroll
+      for (int j = 0; j < UT; ++j) {
+        const int64_t tile = t0 + (int64_t)j * gridDim.x;
+        if (tile < ntiles) {  // block-uniform
+#pragma unroll
+          for (int i = 0; i < NI; ++i) {
+            const int v = tid + 1024 * i;
+            if (NVEC % 1024 == 0 || v < NVEC) {
+#pragma unroll
+              for (int e = 0; e < LV; e += 4)
+                *reinterpret_cast<f32x4*>(&ybar[v * LV + e]) = (f32x4){acc[j][i][e], acc[j][i][e + 1], acc[j][i][e + 2], acc[j][i][e + 3]};
+            }
+          }
+        }
+        __syncthreads();
+        if (tile < ntiles) {
+          float y[M];
+#pragma unroll
+          for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
+          float* zbase = a.Z + tile * 1024 + tid;
+          for (int t = n0; t < n1; ++t) {
+            const int jn = a.grp_nodes[t];
+            const float wj = a.w[jn];
+            float h = y[M - 1];
+#pragma unroll
+            for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
+            __builtin_nontemporal_store(h, zbase + (int64_t)jn * a.ldz);
+          }
+        }
+        __syncthreads();
       }
       solon_phase_align(sync, ++nbar, spin_limit);
     }
@@ -297,7 +383,28 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         done_chunks = nunits * (LV / M);
       }
     } else {
-      const int64_t ntiles = plan->d / (256 * M);
+      const int64_t ptiles = plan->d / (1024 * M);  // block-tiles of 1024 chunks that lie entirely below d
+      const int want_phase = solon_tuning("encode_phase", -1);
+      int phase_grid = 0;
+      constexpr int UT = tile_phase_tiles((1024 * M / LV + 1023) / 1024 * LV);
+      const size_t lds = sizeof(float) * 1024 * M;
+      if (ptiles > 0 && want_phase != 0) {
+        const void* k = (const void*)encode_tile_phase_kernel<M, T>;
+        if (lds <= 64 * 1024 || hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess)
+          phase_grid = solon_resident_grid(k, 1024, lds);
+        else
+          (void)hipGetLastError();
+        const int grid_cap = solon_tuning("encode_phase_grid", 0);
+        if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
+        if (want_phase < 0 && ptiles < 2 * (int64_t)phase_grid * UT) phase_grid = 0;
+      }
+      if (phase_grid > 0) {
+        hipLaunchKernelGGL((encode_tile_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
+                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+        SOLON_HIP(hipGetLastError());
+        done_chunks = ptiles * 1024;
+      }
+      const int64_t ntiles = phase_grid > 0 ? 0 : plan->d / (256 * M);
       if (ntiles > 0) {
         dim3 grid((unsigned)ntiles, (unsigned)q);
         if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a);

@@ -45,16 +45,17 @@ int solon_tuning(const char* key, int fallback) {
 }
 
 // ---------------------------------------------------------------- persistent-grid size
-int solon_resident_grid(const void* kernel, int threads) {
+int solon_resident_grid(const void* kernel, int threads, size_t dynamic_lds) {
   static std::mutex mu;
-  static std::map<const void*, int> cache;
+  static std::map<std::pair<const void*, size_t>, int> cache;
   std::lock_guard<std::mutex> lk(mu);
-  auto it = cache.find(kernel);
+  const auto key = std::make_pair(kernel, dynamic_lds);
+  auto it = cache.find(key);
   if (it != cache.end()) return it->second;
   int dev = 0, cus = 0, per_cu = 0;
   hipFuncAttributes attr;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, dynamic_lds) != hipSuccess ||
       hipFuncGetAttributes(&attr, kernel) != hipSuccess) {
     (void)hipGetLastError();
     return 0;
@@ -62,7 +63,7 @@ int solon_resident_grid(const void* kernel, int threads) {
   // a kernel that spills to scratch memory may get fewer resident waves than the occupancy query promises, and a
   // persistent grid that is not resident all at once only waits out its spin limits: such a build uses the flat kernels
   const int grid = attr.localSizeBytes > 0 ? 0 : cus * per_cu;
-  cache[kernel] = grid;
+  cache[key] = grid;
   return grid;
 }
 

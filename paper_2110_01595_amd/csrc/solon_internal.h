@@ -58,9 +58,10 @@ int solon_hip_fail(hipError_t e, const char* what);
   } while (0)
 
 int solon_tuning(const char* key, int fallback);
-// Number of blocks of `threads` threads of `kernel` that the current device keeps resident at once (0 on error);
+// Number of blocks of `threads` threads (with `dynamic_lds` bytes of dynamic LDS) of `kernel` that the current device keeps
+// resident at once (0 on error, or if the kernel spills to scratch memory);
 // cached per kernel.
-int solon_resident_grid(const void* kernel, int threads);
+int solon_resident_grid(const void* kernel, int threads, size_t dynamic_lds = 0);
 
 // launchers (defined next to their kernels)
 int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st);

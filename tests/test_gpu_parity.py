@@ -154,6 +154,13 @@ def test_phase_separated_kernels(grid):
         run_case(15, 1, 2, 40_002, dtype="bf16", seed=26)
         run_case(7, 1, 1, 20_001, dtype="bf16", seed=27)
         run_case(4, 1, 2, 9, seed=28)                                          # two units in all
+        run_case(100, 5, 10, 150_010, seed=30)                                 # tiled kernels: m does not divide the load width
+        run_case(20, 2, 5, 60_003, seed=31)
+        run_case(9, 1, 3, 30_001, seed=32)
+        run_case(24, 2, 8, 70_001, seed=33)                                    # fp32: 8 does not divide four
+        run_case(20, 2, 5, 60_003, dtype="bf16", seed=34)
+        run_case(100, 5, 10, 150_010, dtype="bf16", attack="mix", dist="student3", sigma=1e-3, seed=35)
+        run_case(64, 0, 16, 70_000, seed=36, u_tol=5e-3)
         gon = [0] * 5 + [-1] + [1] * 6                                          # an idle node: its row stays untouched
         run_case(12, 1, 2, 50_000, group_of_node=gon, group_of_batch=[0] * 6 + [1] * 6, seed=29)
     finally:
