@@ -32,9 +32,19 @@ def windows(d_c):
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("name,u_tol", [("C1", 1e-4), ("C2", 1e-4), ("C3", 1e-4), ("C4", 1e-4), ("C5", 1e-4), ("X1", 1e-4)])
 def test_full_size_config(name, u_tol):
+    check_config(name, workloads.CONFIGS[name], workloads.seeds(name), u_tol)
+
+
+@pytest.mark.timeout(900)
+def test_rows_longer_than_2_to_the_31_elements():
+    """Largest single dimension: gradients of 2^31 + 2052 coordinates (8.6 GB a row), so that every element index
+    beyond a row's start, and every byte offset, leaves 32 bits; d_c = 2^30 + 1026 is not a multiple of four."""
+    cfg = dict(P=4, s=1, m=2, d=2 ** 31 + 2052, dtype="f32", dist="normal", sigma=0.01, attack="flip10")
+    check_config("long-rows", cfg, dict(G=1101, f=2101, byz=3101, attack=4101), 1e-4)
+
+
+def check_config(name, cfg, sd, u_tol):
     t_start = time.time()
-    cfg = workloads.CONFIGS[name]
-    sd = workloads.seeds(name)
     P, s, m, d = cfg["P"], cfg["s"], cfg["m"], cfg["d"]
     say("full-size", name, dict(P=P, s=s, m=m, d=d, dtype=cfg["dtype"], attack=cfg["attack"]))
     plan = solon.Plan(P, s, m, d, dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
