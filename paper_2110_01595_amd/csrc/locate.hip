@@ -10,6 +10,7 @@
 #include <math.h>
 
 #include "solon_internal.h"
+#include "wave_ops.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -273,12 +274,8 @@ __device__ int wave_rank(double v, bool active, int n, int lane) {
   return rank;
 }
 
-// Sum over the wavefront, identical bits in every lane (each butterfly step adds the same two numbers in both lanes).
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
+// Sum over the wavefront, identical bits in every lane.
+__device__ __forceinline__ double wave_sum(double v) { return wave_sum_all(v); }
 
 // Value at this lane's point x of the least-squares polynomial of degree m-1 through the points (x, y) of the lanes
 // with `use` set.  Orthonormal polynomials of the discrete inner product over those points are generated by their
