@@ -20,6 +20,10 @@
  * Streams.  hip_stream is a hipStream_t passed as void* (NULL = the default stream).  All kernels
  * of a call are enqueued on it in order; a call returns without waiting unless it has to hand a
  * result back through a host pointer.  One locate -> decode pair may be in flight per plan.
+ * The calls that take no host output (solon_encode; solon_locate, solon_locate_decode and
+ * solon_decode_majority with NULL host pointers; solon_decode with n_byz < 0) allocate nothing,
+ * issue no memsets and never wait for the host: they can be recorded into a HIP graph and replayed
+ * (run each once eagerly first, so that the one-time occupancy queries are not part of the capture).
  *
  * Errors.  Every function returns SOLON_OK or a negative solon_status; nothing throws or aborts.
  * On error the outputs are unspecified, but no access outside the given extents is made.

@@ -271,6 +271,53 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
         solon.solon_tune("fuse_sample", 1 << 17)
 
 
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """The asynchronous calls allocate nothing, clear nothing with memsets and never wait for the host, so a whole step
+    (encode, then phi and psi) can be recorded once into a HIP graph; every replay - with eager work in between - gives
+    the eager result.  The persistent kernels are forced, so their self-resetting arrival counters go through replays."""
+    cfg = dict(P=63, d=1_200_004, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(63, 3, 4, cfg["d"])
+    G = workloads.make_gradients(cfg, DEV, 71, d=cfg["d"])
+    Z = torch.zeros((63, plan.d_c), dtype=torch.float32, device=DEV)
+    u = torch.zeros(cfg["d"], dtype=torch.float32, device=DEV)
+    f = workloads.make_projection(plan.d_c, DEV, 72)
+    byz = [5, 30, 61]
+    for knob in ("encode_phase", "decode_phase", "fuse"):
+        solon.solon_tune(knob, 1)
+    solon.solon_tune("fuse_sample", 4096)
+    try:
+        solon.solon_encode(plan, G, Z)
+        R = workloads.apply_attack(Z.clone(), byz, "mix", 73)
+        V, _ = solon.solon_locate_decode(plan, R, f, u)                       # eager reference (and warm-up)
+        assert V == byz
+        Z_ref, u_ref = Z.clone(), u.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                solon.solon_encode(plan, G, Z)
+                solon.solon_locate_decode(plan, R, f, u, want_host=False)
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(4):
+            Z.zero_()
+            u.zero_()
+            if rep % 2 == 1:                                                    # eager calls on the same plan between replays
+                solon.solon_locate(plan, R, f, want_host=False)
+                solon.solon_decode(plan, R, u)
+                u.zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(Z, Z_ref), rep
+            assert torch.equal(u, u_ref), rep
+            assert solon.solon_decode_status(plan) == solon.SOLON_OK
+    finally:
+        for knob in ("encode_phase", "decode_phase", "fuse"):
+            solon.solon_tune(knob, -1)
+        solon.solon_tune("fuse_sample", 1 << 17)
+
+
 def test_decode_with_host_supplied_set():
     run_case(31, 2, 2, 20_000, attack="noise100", decode_from_host=True, seed=8)
 
