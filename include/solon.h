@@ -25,6 +25,12 @@
  * issue no memsets and never wait for the host: they can be recorded into a HIP graph and replayed
  * (run each once eagerly first, so that the one-time occupancy queries are not part of the capture).
  *
+ * Alignment.  Any element-aligned pointers and strides are accepted.  The fastest kernels need 16-byte
+ * aligned rows: G, Z / R, f and u aligned to 16 bytes and row strides that are multiples of 16 bytes
+ * (ldg a multiple of 4 fp32 or 8 bf16 elements, ldz / ldr a multiple of 4).  Other layouts (an odd d with
+ * unpadded rows, say) run element-wise kernels at about three quarters of that speed; padding the row
+ * strides is the cheap cure.
+ *
  * Errors.  Every function returns SOLON_OK or a negative solon_status; nothing throws or aborts.
  * On error the outputs are unspecified, but no access outside the given extents is made.
  * solon_last_error() gives a thread-local description of the last failure.

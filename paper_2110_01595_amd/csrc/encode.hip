@@ -348,6 +348,43 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
   }
 }
 
+// The same tiling for rows of G that are not 16-byte aligned (an odd d with unpadded rows, say): the group sum is
+// accumulated element by element - position tid + 256 i of the tile, coalesced 4- or 2-byte loads - so it needs no
+// alignment beyond the element's own, and any m.  Same order of additions.
+template <int M, typename T>
+__global__ __launch_bounds__(256) void encode_tile_elem_kernel(enc_args a) {
+  __shared__ float ybar[256 * M];
+  const int g = blockIdx.y, tid = threadIdx.x;
+  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
+  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int64_t tile = blockIdx.x;
+  const T* base = static_cast<const T*>(a.G) + tile * (256 * M) + tid;
+  float acc[M];
+#pragma unroll
+  for (int i = 0; i < M; ++i) acc[i] = 0.0f;
+#pragma unroll 2
+  for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+    const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+#pragma unroll
+    for (int i = 0; i < M; ++i) acc[i] += elem_to_float(__builtin_nontemporal_load(src + 256 * i));
+  }
+#pragma unroll
+  for (int i = 0; i < M; ++i) ybar[tid + 256 * i] = acc[i];
+  __syncthreads();
+  float y[M];
+#pragma unroll
+  for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
+  float* zbase = a.Z + tile * 256 + tid;
+  for (int t = n0; t < n1; ++t) {
+    const int j = a.grp_nodes[t];
+    const float wj = a.w[j];
+    float h = y[M - 1];
+#pragma unroll
+    for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
+    __builtin_nontemporal_store(h, zbase + (int64_t)j * a.ldz);
+  }
+}
+
 template <int M, typename T>
 static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool aligned, hipStream_t st) {
   constexpr int LV = load_traits<T>::LV;
@@ -414,7 +451,15 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       }
     }
   }
-  if (done_chunks < plan->d_c) {  // ragged tail, or the whole range when rows are not 16-byte aligned
+  if (!aligned && solon_tuning("encode_force_generic", 0) == 0) {  // rows of G without 16-byte alignment
+    const int64_t ntiles = plan->d / (256 * M);
+    if (ntiles > 0) {
+      hipLaunchKernelGGL((encode_tile_elem_kernel<M, T>), dim3((unsigned)ntiles, (unsigned)q), dim3(threads), 0, st, a);
+      SOLON_HIP(hipGetLastError());
+      done_chunks = ntiles * 256;
+    }
+  }
+  if (done_chunks < plan->d_c) {  // ragged tail (or everything, when the generic kernel is forced)
     const int64_t n = plan->d_c - done_chunks;
     int64_t bx = std::min<int64_t>((n + threads - 1) / threads, std::max(1, cap));
     hipLaunchKernelGGL((encode_chunk_kernel<M, T>), dim3((unsigned)bx, (unsigned)q), dim3(threads), 0, st, a, done_chunks,
