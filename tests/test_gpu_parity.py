@@ -318,6 +318,17 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
         solon.solon_tune("fuse_sample", 1 << 17)
 
 
+def test_degenerate_shapes():
+    """No tolerance at all (s = 0: groups of m nodes, nothing to locate, psi inverts the group's own Vandermonde), the
+    plain sum without code (s = 0, m = 1: every node its own group), a single group (P = r), one coordinate."""
+    run_case(5, 0, 1, 10_001, n_byz=0, seed=90)
+    run_case(8, 0, 2, 10_002, n_byz=0, seed=91)
+    run_case(12, 0, 4, 40_004, n_byz=0, seed=92, fused=True)
+    run_case(6, 1, 4, 20_003, seed=93)                      # P = r = 6: one group
+    run_case(3, 1, 1, 1, seed=94)                           # d = 1
+    run_case(14, 5, 4, 8_192, attack="mix", seed=95)        # one group that carries all s = 5 adversaries
+
+
 def test_decode_with_host_supplied_set():
     run_case(31, 2, 2, 20_000, attack="noise100", decode_from_host=True, seed=8)
 
