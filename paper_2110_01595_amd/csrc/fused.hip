@@ -50,8 +50,13 @@ constexpr int fuse_rows(int m) { return m == 4 ? 6 : 8; }
 // Dynamic LDS: one fp64 slot per (wavefront, node).  A wavefront parks the sums of its own columns there row by row,
 // so the loop over the groups needs no block-wide synchronisation (wavefronts that run in lockstep leave HBM idle while they
 // all compute); the block adds the wavefronts' slots in fixed order once per tile.
+// The three small tables come in as separate restrict-qualified read-only arguments so that the compiler may fetch
+// them through the scalar cache (a vector load of a wave-uniform index costs a full memory round trip before the
+// batch's row loads can even be issued).
 template <int M>
-__global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_args a) {
+__global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_args a, const int32_t* __restrict__ grp_off,
+                                                                           const int32_t* __restrict__ order,
+                                                                           const float* __restrict__ coef) {
   constexpr int FUSE_ROWS = fuse_rows(M);
   constexpr int NW = FUSE_BLOCK / 64;
   extern __shared__ double sm[];  // [NW][P]
@@ -80,13 +85,13 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
       for (int e = 0; e < 4 * M; ++e) out[i][e] = 0.0f;
     }
     for (int g = 0; g < a.q; ++g) {
-      const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+      const int n0 = grp_off[g], n1 = grp_off[g + 1];
       float cf[M][M];  // the guessed rows' table, held in scalar registers (wave-uniform)
 #pragma unroll
       for (int t = 0; t < M; ++t)
 #pragma unroll
         for (int l = 0; l < M; ++l)
-          cf[t][l] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(a.coef[(g * M + t) * M + l])));
+          cf[t][l] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(coef[(g * M + t) * M + l])));
       const int nbatch = (n1 - n0 + FUSE_ROWS - 1) / FUSE_ROWS;
       const int per_batch = (n1 - n0 + nbatch - 1) / nbatch;  // batches of equal size, at most FUSE_ROWS rows, at least M
       for (int b0 = n0; b0 < n1; b0 += per_batch) {
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
 #pragma unroll
         for (int r = 0; r < FUSE_ROWS; ++r) {
           acc[r] = 0.0;
-          node[r] = __builtin_amdgcn_readfirstlane(a.order[b0 + min(r, nb - 1)]);  // wave-uniform; a short batch re-reads its last row
+          node[r] = __builtin_amdgcn_readfirstlane(order[b0 + min(r, nb - 1)]);  // wave-uniform; a short batch re-reads its last row
         }
 #pragma unroll
         for (int i = 0; i < FUSE_U; ++i) {
@@ -158,7 +163,7 @@ template <int M>
 static int fused_pass(solon_plan* plan, const fuse_args& a0, int grid, hipStream_t st) {
   fuse_args a = a0;
   const size_t lds = sizeof(double) * (FUSE_BLOCK / 64) * plan->P;
-  hipLaunchKernelGGL((project_recombine_kernel<M>), dim3((unsigned)grid), dim3(FUSE_BLOCK), lds, st, a);
+  hipLaunchKernelGGL((project_recombine_kernel<M>), dim3((unsigned)grid), dim3(FUSE_BLOCK), lds, st, a, a.grp_off, a.order, a.coef);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
