@@ -228,6 +228,9 @@ def test_locate_decode_in_one_pass(grid):
         run_case(100, 5, 4, 24_000, attack="huge", seed=52, fused=True)
         oplan = so.make_plan(63, 3, 4)
         run_case(63, 3, 4, 50_000, attack="mix", byz=oplan.nodes[2][:3].tolist(), seed=53, fused=True)    # all in one group
+        run_case(40, 8, 4, 60_000, attack="mix", seed=56, fused=True)             # groups of 20 nodes: several batches of rows
+        run_case(64, 4, 4, 30_000, attack="mix", seed=57, fused=True, group_of_node=[0] * 64)   # one group of 64 nodes
+        run_case(45, 2, 2, 50_002, attack="noise100", seed=58, fused=True)        # groups of 6 and 7 nodes, m = 2
         run_case(20, 2, 5, 25_003, seed=54, fused=True)                           # m = 5: falls back to the two passes
         run_case(15, 1, 2, 40_002, pad=1, seed=55, fused=True)                    # unaligned rows: falls back
     finally:
