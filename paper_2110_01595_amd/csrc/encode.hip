@@ -46,6 +46,21 @@ __device__ __forceinline__ void load_add(const uint16_t* src, float* acc) {
   acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xffff0000u);
 }
 
+// the same accumulation from 16 bytes already in registers (the tag selects the element type)
+__device__ __forceinline__ void add_raw(const u32x4 v, float* acc, float) {
+  acc[0] += __uint_as_float(v.x); acc[1] += __uint_as_float(v.y); acc[2] += __uint_as_float(v.z); acc[3] += __uint_as_float(v.w);
+}
+__device__ __forceinline__ void add_raw(const u32x4 v, float* acc, uint16_t) {
+  acc[0] += __uint_as_float(v.x << 16); acc[1] += __uint_as_float(v.x & 0xffff0000u);
+  acc[2] += __uint_as_float(v.y << 16); acc[3] += __uint_as_float(v.y & 0xffff0000u);
+  acc[4] += __uint_as_float(v.z << 16); acc[5] += __uint_as_float(v.z & 0xffff0000u);
+  acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xffff0000u);
+}
+
+// word 3 of a raw buffer descriptor on gfx9 (32-bit data format, no swizzle) and the non-temporal bit of the cache policy
+#define SOLON_BUFFER_WORD3 0x00020000
+#define SOLON_BUFFER_NT 2
+
 template <int NC, bool NT>
 __device__ __forceinline__ void store_chunks(float* dst, const float* z) {
   if constexpr (NC % 4 == 0) {
@@ -117,63 +132,97 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nun
 // same order of additions as encode_vec_kernel.
 // units a thread of the phase-separated kernel keeps in registers: as many as leave eight waves per SIMD resident
 template <typename T> struct phase_units;
-template <> struct phase_units<float> { static constexpr int U = 6; };
+template <> struct phase_units<float> { static constexpr int U = 8; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
 
 // block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within 32 registers
 constexpr int tile_phase_tiles(int sums_per_tile) { return 32 / sums_per_tile > 0 ? 32 / sums_per_tile : 1; }
 
 template <int M, typename T>
-__global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit) {
+__global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit, uint32_t pace8,
+                         const int32_t* __restrict__ grp_off, const int32_t* __restrict__ grp_nodes, const int32_t* __restrict__ bat_off,
+                         const int32_t* __restrict__ grp_batches, const float* __restrict__ w) {
+  // the small tables come in as read-only, non-aliased kernel arguments of their own: the compiler then fetches them
+  // with scalar loads, which do not share a counter with the vector stores (a vector load of w_j would make every row
+  // of the write phase wait for all stores before it)
   constexpr int LV = load_traits<T>::LV;
   constexpr int NC = LV / M;
   constexpr int U = phase_units<T>::U;
-  const T* G = static_cast<const T*>(a.G);
-  const int64_t span = (int64_t)gridDim.x * blockDim.x;
-  const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t per_phase = span * U;
+  // In a phase, thread t of the grid owns units t, t + span, .., t + (U-1) span counted from the phase's first unit.
+  // The rows of G are read through buffer descriptors: position i of a row gets one of its own - wave-uniform base
+  // (row, phase, i), bytes left in the row from there (at most one span) - and the lane offset is the same 32-bit
+  // t * 16 for all of them, so no 64-bit lane addresses are kept, and the hardware range check makes the ragged last
+  // phase branch-free: a load past the end of the row returns zeros (never used).
+  __shared__ int s_node[SOLON_MAX_GROUP], s_batch[SOLON_MAX_GROUP];
+  __shared__ float s_w[SOLON_MAX_GROUP];
+  const uint32_t span = gridDim.x * blockDim.x;  // the host checks span * 16 < 2^32
+  const uint32_t gtid = blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_phase = (int64_t)span * U;
   const int nphase = (int)((nunits + per_phase - 1) / per_phase);
+  constexpr uint32_t ZB = NC * sizeof(float);  // bytes of Z per unit
   uint32_t nbar = 0;
   for (int g = 0; g < q; ++g) {
-    const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-    const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+    const int b0 = bat_off[g], b1 = bat_off[g + 1];
+    const int n0 = grp_off[g], n1 = grp_off[g + 1];
+    // the group's tables go to LDS once: fetched from memory in the middle of a phase, each would cost a wave a
+    // round trip through the busy memory system per row (two in a chain for w_j).  The previous group's last
+    // alignment point separates these writes from its reads, the first one below separates them from the reads here.
+    if ((int)threadIdx.x < n1 - n0) {
+      const int j = grp_nodes[n0 + threadIdx.x];
+      s_node[threadIdx.x] = j;
+      s_w[threadIdx.x] = w[j];
+    }
+    const bool staged = b1 - b0 <= SOLON_MAX_GROUP;  // a group may own any number of batches, the table holds this many
+    if (staged && (int)threadIdx.x < b1 - b0) s_batch[threadIdx.x] = grp_batches[b0 + threadIdx.x];
+    __syncthreads();
     for (int ph = 0; ph < nphase; ++ph) {
-      const int64_t u0 = (int64_t)ph * per_phase + gtid;
+      const int64_t ubase = (int64_t)ph * per_phase;  // first unit of the phase
+      uint32_t have[U];                               // units of position i that lie inside the row
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        const int64_t left = nunits - ubase - (int64_t)i * span;
+        have[i] = left <= 0 ? 0u : left < (int64_t)span ? (uint32_t)left : span;
+      }
+      char* gph = const_cast<char*>(static_cast<const char*>(a.G)) + ubase * 16;
       float acc[U][LV];
 #pragma unroll
       for (int i = 0; i < U; ++i)
 #pragma unroll
         for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
-      for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-        const T* src = G + (int64_t)a.grp_batches[k] * a.ldg;
+      for (int k = 0; k < b1 - b0; ++k) {  // group sum, in batch order
+        const int batch = staged ? __builtin_amdgcn_readfirstlane(s_batch[k]) : grp_batches[b0 + k];
+        char* src = gph + (int64_t)batch * a.ldg * (int64_t)sizeof(T);
+        // one load in flight per wave: with all U of a row in flight the kernel measured 2 to 7 % slower, the chip then
+        // reads from U spans of the row at once instead of moving through them in step
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-          int64_t u = u0 + (int64_t)i * span;
-          u = u < nunits ? u : nunits - 1;  // past the end: reload the last unit (in bounds, result unused) rather than branch
-          load_add<true>(src + u * LV, acc[i]);
+          const __amdgpu_buffer_rsrc_t piece = __builtin_amdgcn_make_buffer_rsrc(src + (int64_t)i * span * 16, 0, have[i] * 16u, SOLON_BUFFER_WORD3);
+          add_raw(__builtin_amdgcn_raw_buffer_load_b128(piece, gtid * 16u, 0, SOLON_BUFFER_NT), acc[i], T());
         }
       }
       solon_phase_align(sync, ++nbar, spin_limit);
-      for (int t = n0; t < n1; ++t) {
-        const int j = a.grp_nodes[t];
-        const float wj = a.w[j];
-        float* zrow = a.Z + (int64_t)j * a.ldz;
+      const unsigned long long t0 = pace8 ? wall_clock64() : 0ull;
+      uint32_t step = 0;
+      char* zph = reinterpret_cast<char*>(a.Z + ubase * NC);
+      for (int t = 0; t < n1 - n0; ++t) {
+        const int j = __builtin_amdgcn_readfirstlane(s_node[t]);
+        const float wj = s_w[t];
+        char* zrow = zph + (int64_t)j * a.ldz * (int64_t)sizeof(float);
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-          const int64_t u = u0 + (int64_t)i * span;
-          if (u < nunits) {
-            float z[NC];
+          if (pace8) solon_pace(t0, step++, pace8);  // step (t, i) of all waves covers one contiguous window of row j
+          float z[NC];
 #pragma unroll
-            for (int c = 0; c < NC; ++c) {
-              float h = acc[i][c * M + M - 1];
+          for (int c = 0; c < NC; ++c) {
+            float h = acc[i][c * M + M - 1];
 #pragma unroll
-              for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, acc[i][c * M + l]);  // Horner in w_j
-              z[c] = h;
-            }
-            store_chunks<NC, true>(zrow + u * NC, z);
+            for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, acc[i][c * M + l]);  // Horner in w_j
+            z[c] = h;
           }
-          // one store in flight per wave, so that HBM is handed the addresses close to the order they were issued in
-          // (measured: 0 to 1.5 % faster than with all of a wave's stores queued at once)
+          // plain global stores: the same stores through a buffer descriptor measured 2.7 % slower on the whole kernel
+          if (gtid < have[i]) store_chunks<NC, true>(reinterpret_cast<float*>(zrow + (int64_t)i * span * ZB + (size_t)gtid * ZB), z);
+          // one store in flight per wave: a wave whose store HBM has not taken yet does not add the next one to the
+          // queues, whatever the schedule says (without this wait a pace a few percent too fast costs 5 %)
           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
       }
@@ -405,10 +454,12 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
         const int64_t per_phase = (int64_t)phase_grid * 1024 * phase_units<T>::U;
         if (want_phase < 0 && nunits < 2 * per_phase) phase_grid = 0;
+        if ((int64_t)phase_grid * 1024 * 16 >= ((int64_t)1 << 32)) phase_grid = 0;  // the kernel's 32-bit byte offsets inside a span
       }
       if (phase_grid > 0) {
-        hipLaunchKernelGGL((encode_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), 0, st, a, nunits, q,
-                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+        const uint32_t pace8 = solon_store_pace8((int64_t)phase_grid * 1024 * (LV / M) * (int64_t)sizeof(float));
+        hipLaunchKernelGGL((encode_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), 0, st, a, nunits, q, plan->dev.grid_sync,
+                           solon_tuning("phase_spin_limit", 400), pace8, a.grp_off, a.grp_nodes, a.bat_off, a.grp_batches, a.w);
         SOLON_HIP(hipGetLastError());
         done_chunks = nunits * (LV / M);
       } else if (nunits > 0) {

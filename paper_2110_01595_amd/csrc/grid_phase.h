@@ -36,6 +36,23 @@ __device__ __forceinline__ void solon_phase_align(uint32_t* sync, uint32_t nbar,
   __syncthreads();
 }
 
+// Store pacing inside a write phase.  HBM takes writes fastest when the addresses in flight chip-wide stay inside a
+// few megabytes: a flat fill whose 4 KB pieces are shuffled inside 1 MB windows runs as fast as an ordered one, shuffled
+// inside 64 MB windows it loses 20 %.  In a write phase every wave has a list of store steps (row after row) and step
+// k of all waves together covers one contiguous window, but waves that get their stores accepted early run ahead into
+// later windows.  Holding step k of every wave back until k * (window bytes / absorbable rate) after the phase began
+// keeps the chip inside one or two windows; waves that HBM delays simply lag (the caller also lets a wave wait for
+// its previous store before the next).  `pace8` is that interval in eighths of a tick of the constant-rate clock,
+// t0 the clock when the wave entered the phase.  The wait is bounded by the clock and by a poll count.
+__device__ __forceinline__ void solon_pace(unsigned long long t0, uint32_t step, uint32_t pace8) {
+  const unsigned long long due = t0 + (((unsigned long long)step * pace8) >> 3);
+  int n = 0;
+  while (wall_clock64() < due && n < 256) {
+    __builtin_amdgcn_s_sleep(1);
+    ++n;
+  }
+}
+
 // Called once by every block after its last alignment point: the last block to leave zeroes the counters, so
 // the next launch (ordered after this one on its stream) starts from zero without a separate clearing step.
 __device__ __forceinline__ void solon_phase_exit(uint32_t* sync) {

@@ -62,6 +62,9 @@ int solon_tuning(const char* key, int fallback);
 // resident at once (0 on error, or if the kernel spills to scratch memory);
 // cached per kernel.
 int solon_resident_grid(const void* kernel, int threads, size_t dynamic_lds = 0);
+// interval between store steps of a paced write phase whose steps cover `step_bytes` each chip-wide, in eighths of a
+// tick of the device's constant-rate clock (0: pacing off or clock rate unknown); knob "store_pace_gbps"
+uint32_t solon_store_pace8(int64_t step_bytes);
 
 // launchers (defined next to their kernels)
 int solon_launch_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, hipStream_t st);
