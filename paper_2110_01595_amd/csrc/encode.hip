@@ -22,6 +22,15 @@ struct enc_args {
   const float* w;
 };
 
+// The small tables reach every kernel as read-only, non-aliased kernel arguments of their own (a pointer inside the
+// argument struct cannot carry that promise): the compiler then fetches them with scalar loads, which do not share a
+// counter with the vector loads and stores - a vector load of w_j would make every row's store wait for all stores
+// before it.
+#define ENC_TABLE_PARAMS                                                                                             \
+  const int32_t *__restrict__ grp_off, const int32_t *__restrict__ grp_nodes, const int32_t *__restrict__ bat_off, \
+      const int32_t *__restrict__ grp_batches, const float *__restrict__ w
+#define ENC_TABLE_ARGS(a) (a).grp_off, (a).grp_nodes, (a).bat_off, (a).grp_batches, (a).w
+
 __device__ __forceinline__ float elem_to_float(float v) { return v; }
 __device__ __forceinline__ float elem_to_float(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }  // bf16 widens exactly
 
@@ -87,13 +96,13 @@ __device__ __forceinline__ void store_chunks(float* dst, const float* z) {
 // i.e. NC = UE / m whole chunks; blockIdx.y is the group.  Requires 16-byte aligned rows of G and rows of Z
 // aligned to the NC floats (at most four) a thread stores at once.
 template <int M, int UE, typename T, bool NT>
-__global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nunits) {
+__global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nunits, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NL = UE / LV;
   constexpr int NC = UE / M;
   const int g = blockIdx.y;
-  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int b0 = bat_off[g], b1 = bat_off[g + 1];
+  const int n0 = grp_off[g], n1 = grp_off[g + 1];
   const T* G = static_cast<const T*>(a.G);
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < nunits; u += stride) {
@@ -103,14 +112,14 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nun
     const T* base = G + u * UE;
 #pragma unroll 4
     for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-      const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+      const T* src = base + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
       for (int v = 0; v < NL; ++v) load_add<NT>(src + v * LV, acc + v * LV);
     }
     float* zbase = a.Z + u * NC;
     for (int t = n0; t < n1; ++t) {  // one message element per node of the group and chunk
-      const int j = a.grp_nodes[t];
-      const float wj = a.w[j];
+      const int j = grp_nodes[t];
+      const float wj = w[j];
       float z[NC];
 #pragma unroll
       for (int c = 0; c < NC; ++c) {
@@ -139,12 +148,7 @@ template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
 constexpr int tile_phase_tiles(int sums_per_tile) { return 32 / sums_per_tile > 0 ? 32 / sums_per_tile : 1; }
 
 template <int M, typename T>
-__global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit, uint32_t pace8,
-                         const int32_t* __restrict__ grp_off, const int32_t* __restrict__ grp_nodes, const int32_t* __restrict__ bat_off,
-                         const int32_t* __restrict__ grp_batches, const float* __restrict__ w) {
-  // the small tables come in as read-only, non-aliased kernel arguments of their own: the compiler then fetches them
-  // with scalar loads, which do not share a counter with the vector stores (a vector load of w_j would make every row
-  // of the write phase wait for all stores before it)
+__global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit, uint32_t pace8, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NC = LV / M;
   constexpr int U = phase_units<T>::U;
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
 // the m coefficients of its own chunk and writes one message element per node.  Same order of additions as
 // encode_tile_kernel.
 template <int M, typename T>
-__global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, int64_t ntiles, int q, uint32_t* sync, int spin_limit) {
+__global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, int64_t ntiles, int q, uint32_t* sync, int spin_limit, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NVEC = 1024 * M / LV;           // 16-byte vectors per row and block-tile (1024 m is a multiple of LV)
   constexpr int NI = (NVEC + 1023) / 1024;      // vectors per thread and block-tile
@@ -250,8 +254,8 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
   const int nphase = (int)((ntiles + per_phase - 1) / per_phase);
   uint32_t nbar = 0;
   for (int g = 0; g < q; ++g) {
-    const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-    const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+    const int b0 = bat_off[g], b1 = bat_off[g + 1];
+    const int n0 = grp_off[g], n1 = grp_off[g + 1];
     for (int ph = 0; ph < nphase; ++ph) {
       // tile j of this block in this phase: consecutive blocks take consecutive tiles
       const int64_t t0 = (int64_t)ph * per_phase + blockIdx.x;
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
 #pragma unroll
           for (int e = 0; e < LV; ++e) acc[j][i][e] = 0.0f;
       for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-        const T* row = static_cast<const T*>(a.G) + (int64_t)a.grp_batches[k] * a.ldg;
+        const T* row = static_cast<const T*>(a.G) + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
         for (int j = 0; j < UT; ++j) {
           int64_t tile = t0 + (int64_t)j * gridDim.x;
@@ -299,8 +303,8 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
           for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
           float* zbase = a.Z + tile * 1024 + tid;
           for (int t = n0; t < n1; ++t) {
-            const int jn = a.grp_nodes[t];
-            const float wj = a.w[jn];
+            const int jn = grp_nodes[t];
+            const float wj = w[jn];
             float h = y[M - 1];
 #pragma unroll
             for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
@@ -317,10 +321,10 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
 
 // General path: any alignment, any d; a thread owns one chunk p in [p0, p1).
 template <int M, typename T>
-__global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p0, int64_t p1) {
+__global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p0, int64_t p1, ENC_TABLE_PARAMS) {
   const int g = blockIdx.y;
-  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int b0 = bat_off[g], b1 = bat_off[g + 1];
+  const int n0 = grp_off[g], n1 = grp_off[g + 1];
   const T* G = static_cast<const T*>(a.G);
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (int64_t p = p0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < p1; p += stride) {
@@ -328,14 +332,14 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
 #pragma unroll
     for (int l = 0; l < M; ++l) y[l] = 0.0f;
     for (int k = b0; k < b1; ++k) {
-      const T* src = G + (int64_t)a.grp_batches[k] * a.ldg + p * M;
+      const T* src = G + (int64_t)grp_batches[k] * a.ldg + p * M;
 #pragma unroll
       for (int l = 0; l < M; ++l)
         if (p * M + l < a.d) y[l] += elem_to_float(src[l]);  // coordinates past d count as zero
     }
     for (int t = n0; t < n1; ++t) {
-      const int j = a.grp_nodes[t];
-      const float wj = a.w[j];
+      const int j = grp_nodes[t];
+      const float wj = w[j];
       float h = y[M - 1];
 #pragma unroll
       for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);
@@ -349,14 +353,14 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
 // loads (that part does not depend on m), parked in LDS, and then each thread picks up the m coefficients of its
 // own chunk and writes one message element per node (coalesced 4-byte stores).
 template <int M, typename T, bool NT>
-__global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
+__global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NVEC = 256 * M / LV;          // 16-byte vectors per row and tile
   constexpr int NI = (NVEC + 255) / 256;      // vectors per thread
   __shared__ float ybar[256 * M];
   const int g = blockIdx.y, tid = threadIdx.x;
-  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int b0 = bat_off[g], b1 = bat_off[g + 1];
+  const int n0 = grp_off[g], n1 = grp_off[g + 1];
   const int64_t tile = blockIdx.x;
   const T* base = static_cast<const T*>(a.G) + tile * (256 * M);
   float acc[NI][LV];
@@ -366,7 +370,7 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
     for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
 #pragma unroll 2
   for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-    const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+    const T* src = base + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int v = tid + 256 * i;
@@ -388,8 +392,8 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
   for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
   float* zbase = a.Z + tile * 256 + tid;
   for (int t = n0; t < n1; ++t) {
-    const int j = a.grp_nodes[t];
-    const float wj = a.w[j];
+    const int j = grp_nodes[t];
+    const float wj = w[j];
     float h = y[M - 1];
 #pragma unroll
     for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
@@ -401,11 +405,11 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a) {
 // accumulated element by element - position tid + 256 i of the tile, coalesced 4- or 2-byte loads - so it needs no
 // alignment beyond the element's own, and any m.  Same order of additions.
 template <int M, typename T>
-__global__ __launch_bounds__(256) void encode_tile_elem_kernel(enc_args a) {
+__global__ __launch_bounds__(256) void encode_tile_elem_kernel(enc_args a, ENC_TABLE_PARAMS) {
   __shared__ float ybar[256 * M];
   const int g = blockIdx.y, tid = threadIdx.x;
-  const int b0 = a.bat_off[g], b1 = a.bat_off[g + 1];
-  const int n0 = a.grp_off[g], n1 = a.grp_off[g + 1];
+  const int b0 = bat_off[g], b1 = bat_off[g + 1];
+  const int n0 = grp_off[g], n1 = grp_off[g + 1];
   const int64_t tile = blockIdx.x;
   const T* base = static_cast<const T*>(a.G) + tile * (256 * M) + tid;
   float acc[M];
@@ -413,7 +417,7 @@ __global__ __launch_bounds__(256) void encode_tile_elem_kernel(enc_args a) {
   for (int i = 0; i < M; ++i) acc[i] = 0.0f;
 #pragma unroll 2
   for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-    const T* src = base + (int64_t)a.grp_batches[k] * a.ldg;
+    const T* src = base + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
     for (int i = 0; i < M; ++i) acc[i] += elem_to_float(__builtin_nontemporal_load(src + 256 * i));
   }
@@ -425,8 +429,8 @@ __global__ __launch_bounds__(256) void encode_tile_elem_kernel(enc_args a) {
   for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
   float* zbase = a.Z + tile * 256 + tid;
   for (int t = n0; t < n1; ++t) {
-    const int j = a.grp_nodes[t];
-    const float wj = a.w[j];
+    const int j = grp_nodes[t];
+    const float wj = w[j];
     float h = y[M - 1];
 #pragma unroll
     for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
@@ -459,14 +463,14 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       if (phase_grid > 0) {
         const uint32_t pace8 = solon_store_pace8((int64_t)phase_grid * 1024 * (LV / M) * (int64_t)sizeof(float));
         hipLaunchKernelGGL((encode_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), 0, st, a, nunits, q, plan->dev.grid_sync,
-                           solon_tuning("phase_spin_limit", 400), pace8, a.grp_off, a.grp_nodes, a.bat_off, a.grp_batches, a.w);
+                           solon_tuning("phase_spin_limit", 400), pace8, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = nunits * (LV / M);
       } else if (nunits > 0) {
         int64_t bx = std::min<int64_t>((nunits + threads - 1) / threads, std::max(1, cap));
         dim3 grid((unsigned)bx, (unsigned)q);
-        if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, true>), grid, dim3(threads), 0, st, a, nunits);
-        else hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, false>), grid, dim3(threads), 0, st, a, nunits);
+        if (nt) hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, true>), grid, dim3(threads), 0, st, a, nunits, ENC_TABLE_ARGS(a));
+        else hipLaunchKernelGGL((encode_vec_kernel<M, LV, T, false>), grid, dim3(threads), 0, st, a, nunits, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = nunits * (LV / M);
       }
@@ -488,15 +492,15 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       }
       if (phase_grid > 0) {
         hipLaunchKernelGGL((encode_tile_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
-                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400));
+                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = ptiles * 1024;
       }
       const int64_t ntiles = phase_grid > 0 ? 0 : plan->d / (256 * M);
       if (ntiles > 0) {
         dim3 grid((unsigned)ntiles, (unsigned)q);
-        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a);
-        else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a);
+        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, ENC_TABLE_ARGS(a));
+        else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = ntiles * 256;
       }
@@ -505,7 +509,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
   if (!aligned && solon_tuning("encode_force_generic", 0) == 0) {  // rows of G without 16-byte alignment
     const int64_t ntiles = plan->d / (256 * M);
     if (ntiles > 0) {
-      hipLaunchKernelGGL((encode_tile_elem_kernel<M, T>), dim3((unsigned)ntiles, (unsigned)q), dim3(threads), 0, st, a);
+      hipLaunchKernelGGL((encode_tile_elem_kernel<M, T>), dim3((unsigned)ntiles, (unsigned)q), dim3(threads), 0, st, a, ENC_TABLE_ARGS(a));
       SOLON_HIP(hipGetLastError());
       done_chunks = ntiles * 256;
     }
@@ -514,7 +518,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
     const int64_t n = plan->d_c - done_chunks;
     int64_t bx = std::min<int64_t>((n + threads - 1) / threads, std::max(1, cap));
     hipLaunchKernelGGL((encode_chunk_kernel<M, T>), dim3((unsigned)bx, (unsigned)q), dim3(threads), 0, st, a, done_chunks,
-                       plan->d_c);
+                       plan->d_c, ENC_TABLE_ARGS(a));
     SOLON_HIP(hipGetLastError());
   }
   return SOLON_OK;

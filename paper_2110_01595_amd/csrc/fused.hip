@@ -10,12 +10,11 @@
 // sample is avoided, so the second pass is needed only against an adversary that corrupts nothing but columns
 // outside the sample.  The located set and the status never depend on the guess.
 //
-// The pass is a persistent grid; each time round a thread takes FUSE_U float4 column units through all groups: fp64
-// partial projections of every row (reduced over each wavefront by lane permutations, over the block through LDS,
-// one partial per block, round and row, summed in fixed order afterwards) and the fp32 recombination of the
-// guessed rows, kept in registers and stored at the end of the round.  Writes are 4 % of the traffic here, and waiting
-// for the whole chip at the alignment points, as the encoder does, was measured to buy nothing for this pass: the spin
-// limit defaults to zero, which leaves a block-wide pause between a block's reads and its stores and nothing more.
+// The pass is a persistent grid; each round a thread takes one float4 column unit through all rows: the fp64 partial
+// projection of every row (reduced over each wavefront by lane permutations, over the block through LDS, one partial
+// per block, round and row, summed in fixed order afterwards) and the fp32 recombination of the guessed rows, kept in
+// registers and stored at the end of the round.  After its stores a block waits for the whole chip (bounded), so that
+// all blocks start the next round's rows together.
 #include <algorithm>
 #include <vector>
 
@@ -25,7 +24,6 @@
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#define FUSE_U 2      // float4 column units per thread and phase
 #define FUSE_BLOCK 1024
 #define FUSE_SAMPLE (1 << 17)  // columns of the sample projection behind the guess
 
@@ -42,98 +40,89 @@ struct fuse_args {
   float* u;
   uint32_t* sync;
   int spin_limit;
+  int stage_off;  // floats from the start of dynamic LDS to the store-staging area
 };
 
-// rows of R loaded back to back: as many as leave four waves per SIMD resident without spills
-constexpr int fuse_rows(int m) { return m == 4 ? 6 : 8; }
+// The pass.  Every thread owns one float4 column unit per round and walks all rows of R with a single load in
+// flight, eight waves per SIMD resident: the whole chip then moves through a row's span together and on to the next
+// row, which is the access order HBM serves fastest (the encoder's read phase runs the same way; an earlier version
+// with six to eight rows in flight per lane and half the waves was 9 % slower).  Rows are read through buffer
+// descriptors (wave-uniform base, 32-bit lane offset, hardware range check: past the end of the row a load returns
+// zeros and f is zero there too).  The three small tables are copied to LDS once.
+#define ROWS_WORD3 0x00020000  // word 3 of a raw buffer descriptor on gfx9: 32-bit data format, no swizzle
+#define ROWS_NT 2              // non-temporal bit of the cache policy
 
-// Dynamic LDS: one fp64 slot per (wavefront, node).  A wavefront parks the sums of its own columns there row by row,
-// so the loop over the groups needs no block-wide synchronisation (wavefronts that run in lockstep leave HBM idle while they
-// all compute); the block adds the wavefronts' slots in fixed order once per tile.
-// The three small tables come in as separate restrict-qualified read-only arguments so that the compiler may fetch
-// them through the scalar cache (a vector load of a wave-uniform index costs a full memory round trip before the
-// batch's row loads can even be issued).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <int M>
-__global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_args a, const int32_t* __restrict__ grp_off,
-                                                                           const int32_t* __restrict__ order,
-                                                                           const float* __restrict__ coef) {
-  constexpr int FUSE_ROWS = fuse_rows(M);
+__global__ __launch_bounds__(FUSE_BLOCK, 8) void project_recombine_kernel(fuse_args a, const int32_t* __restrict__ grp_off,
+                                                                                const int32_t* __restrict__ order,
+                                                                                const float* __restrict__ coef) {
   constexpr int NW = FUSE_BLOCK / 64;
-  extern __shared__ double sm[];  // [NW][P]
+  extern __shared__ double sm[];  // [NW][P] sums, then P node indices, q + 1 group offsets, q M M coefficients
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   double* mine = sm + wave * a.P;
-  // Pass ph of the grid covers the units [ph, ph + 1) * span * FUSE_U; for a fixed i the whole grid reads one contiguous
-  // span of every row (measured: 2.23 ms at P = 100, d = 124 M, against 2.37 ms with one contiguous tile per block)
-  const int64_t span = (int64_t)gridDim.x * FUSE_BLOCK;
-  const int64_t gtid = (int64_t)blockIdx.x * FUSE_BLOCK + tid;
-  const int npass = (int)((a.nunits + span * FUSE_U - 1) / (span * FUSE_U));
+  int* s_order = reinterpret_cast<int*>(sm + NW * a.P);
+  int* s_off = s_order + a.P;
+  float* s_coef = reinterpret_cast<float*>(s_off + a.q + 1);
+  float* s_stage = reinterpret_cast<float*>(sm) + a.stage_off;  // [NW][256], 16-byte aligned
+  for (int n = tid; n < a.P; n += FUSE_BLOCK) s_order[n] = order[n];
+  for (int n = tid; n <= a.q; n += FUSE_BLOCK) s_off[n] = grp_off[n];
+  for (int n = tid; n < a.q * M * M; n += FUSE_BLOCK) s_coef[n] = coef[n];
+  __syncthreads();
+  const uint32_t span = gridDim.x * FUSE_BLOCK;  // the launcher keeps span * 16 below 2^32
+  const uint32_t gtid = blockIdx.x * FUSE_BLOCK + tid;
+  const int npass = (int)((a.nunits + span - 1) / span);
   uint32_t nbar = 0;
   for (int ph = 0; ph < npass; ++ph) {
+    const int64_t ubase = (int64_t)ph * span;  // first unit of the round
+    const int64_t left = a.nunits - ubase;
+    const uint32_t have = left < (int64_t)span ? (uint32_t)left : span;  // units of the round inside the rows, at least one
     const int64_t tl = (int64_t)ph * gridDim.x + blockIdx.x;
-    uint32_t off[FUSE_U];  // first column of the unit (the launcher keeps 4 nunits below 2^32); past the end: the last
-    bool valid[FUSE_U];    // unit again, with f = 0 (adds exact zeros)
-    f32x4 fv[FUSE_U];
-    float out[FUSE_U][4 * M];
-#pragma unroll
-    for (int i = 0; i < FUSE_U; ++i) {
-      const int64_t unit = (int64_t)ph * span * FUSE_U + i * span + gtid;
-      valid[i] = unit < a.nunits;
-      off[i] = (uint32_t)(4 * (valid[i] ? unit : a.nunits - 1));
-      fv[i] = *reinterpret_cast<const f32x4*>(a.f + off[i]);
-      if (!valid[i]) fv[i] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-      for (int e = 0; e < 4 * M; ++e) out[i][e] = 0.0f;
+    double f0, f1, f2, f3;
+    {
+      const __amdgpu_buffer_rsrc_t fd = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.f) + ubase * 4, 0, have * 16u, ROWS_WORD3);
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(fd, gtid * 16u, 0, 0);
+      f0 = __uint_as_float(v.x); f1 = __uint_as_float(v.y); f2 = __uint_as_float(v.z); f3 = __uint_as_float(v.w);
     }
+    float out[4 * M];
+#pragma unroll
+    for (int e = 0; e < 4 * M; ++e) out[e] = 0.0f;
+    float* rph = const_cast<float*>(a.R) + ubase * 4;
+    // The rows in the order of the table (group after group, a group's guessed rows first).  The load of the next
+    // row is issued as soon as the current row's has arrived and before its arithmetic, so that a wave has one load
+    // in flight all the time rather than none while it reduces.
+    int node = __builtin_amdgcn_readfirstlane(s_order[0]);
+    u32x4 ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, ROWS_WORD3),
+                                                        gtid * 16u, 0, ROWS_NT);
+    int t = 0;
     for (int g = 0; g < a.q; ++g) {
-      const int n0 = grp_off[g], n1 = grp_off[g + 1];
-      float cf[M][M];  // the guessed rows' table, held in scalar registers (wave-uniform)
-#pragma unroll
-      for (int t = 0; t < M; ++t)
-#pragma unroll
-        for (int l = 0; l < M; ++l)
-          cf[t][l] = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(coef[(g * M + t) * M + l])));
-      const int nbatch = (n1 - n0 + FUSE_ROWS - 1) / FUSE_ROWS;
-      const int per_batch = (n1 - n0 + nbatch - 1) / nbatch;  // batches of equal size, at most FUSE_ROWS rows, at least M
-      for (int b0 = n0; b0 < n1; b0 += per_batch) {
-        const int nb = min(per_batch, n1 - b0);
-        double acc[FUSE_ROWS];
-        int node[FUSE_ROWS];
-#pragma unroll
-        for (int r = 0; r < FUSE_ROWS; ++r) {
-          acc[r] = 0.0;
-          node[r] = __builtin_amdgcn_readfirstlane(order[b0 + min(r, nb - 1)]);  // wave-uniform; a short batch re-reads its last row
+      const int n0 = __builtin_amdgcn_readfirstlane(s_off[g]), n1 = __builtin_amdgcn_readfirstlane(s_off[g + 1]);
+      for (; t < n1; ++t) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        const u32x4 raw = ahead;
+        const int cur = node;
+        if (t + 1 < a.P) {
+          node = __builtin_amdgcn_readfirstlane(s_order[t + 1]);
+          ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, ROWS_WORD3),
+                                                        gtid * 16u, 0, ROWS_NT);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        const float v[4] = {__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z), __uint_as_float(raw.w)};
+        double acc = f0 * (double)v[0];
+        acc = fma(f1, (double)v[1], acc);
+        acc = fma(f2, (double)v[2], acc);
+        acc = fma(f3, (double)v[3], acc);
+        if (t - n0 < M) {  // one of the group's guessed rows: its share of the recombination
 #pragma unroll
-        for (int i = 0; i < FUSE_U; ++i) {
-          f32x4 rv[FUSE_ROWS];
+          for (int l = 0; l < M; ++l) {
+            const float cf = s_coef[(g * M + (t - n0)) * M + l];
 #pragma unroll
-          for (int r = 0; r < FUSE_ROWS; ++r)
-            rv[r] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.R + (int64_t)node[r] * a.ldr + off[i]));
-          const double f0 = fv[i].x, f1 = fv[i].y, f2 = fv[i].z, f3 = fv[i].w;
-#pragma unroll
-          for (int r = 0; r < FUSE_ROWS; ++r) {  // projection, fp64
-            acc[r] = fma(f0, (double)rv[r].x, acc[r]);
-            acc[r] = fma(f1, (double)rv[r].y, acc[r]);
-            acc[r] = fma(f2, (double)rv[r].z, acc[r]);
-            acc[r] = fma(f3, (double)rv[r].w, acc[r]);
+            for (int c = 0; c < 4; ++c) out[c * M + l] = fmaf(cf, v[c], out[c * M + l]);
           }
-          if (b0 == n0) {  // the group's first batch starts with the M guessed rows: their recombination
-#pragma unroll
-            for (int t = 0; t < M; ++t) {
-              const float v[4] = {rv[t].x, rv[t].y, rv[t].z, rv[t].w};
-#pragma unroll
-              for (int l = 0; l < M; ++l)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) out[i][c * M + l] = fmaf(cf[t][l], v[c], out[i][c * M + l]);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);  // one unit's rows in registers at a time: hoisting the next unit's loads spills
         }
-#pragma unroll
-        for (int r = 0; r < FUSE_ROWS; ++r) {  // this wavefront's share of rho
-          const double v = wave_sum_lane63(acc[r]);
-          if (lane == 63 && r < nb) mine[node[r]] = v;
-        }
+        const double sum = wave_sum_lane63(acc);
+        if (lane == 63) mine[cur] = sum;
       }
     }
     __syncthreads();
@@ -144,33 +133,54 @@ __global__ __launch_bounds__(FUSE_BLOCK, 4) void project_recombine_kernel(fuse_a
       for (int w = 1; w < NW; ++w) v += sm[w * a.P + n];
       tile[n] = v;
     }
-    solon_phase_align(a.sync, ++nbar, a.spin_limit);
+    // u: a wavefront owns 64 units = 256 M consecutive floats, a lane 4 M of them.  Stored straight from the lanes'
+    // registers every store instruction would scatter 16-byte pieces 16 M bytes apart (measured: 1.6 TB/s for these
+    // 4 % of the traffic, 14 % of the pass); instead the sums go through LDS, 64 / M lanes' worth at a time, and each
+    // store instruction writes 1 KB without gaps.
+    if constexpr (M == 1) {
+      if (gtid < have) __builtin_nontemporal_store((f32x4){out[0], out[1], out[2], out[3]}, reinterpret_cast<f32x4*>(a.u + (ubase + gtid) * 4));
+    } else {
+      float* stage = s_stage + wave * 256;
+      float* wave_u = a.u + (ubase + (gtid - lane)) * (int64_t)(4 * M);
 #pragma unroll
-    for (int i = 0; i < FUSE_U; ++i) {
-      if (valid[i]) {
-        float* dst = a.u + (int64_t)off[i] * M;
+      for (int k = 0; k < M; ++k) {
+        if (lane / (64 / M) == k) {
 #pragma unroll
-        for (int e = 0; e < 4 * M; e += 4)
-          *reinterpret_cast<f32x4*>(dst + e) = (f32x4){out[i][e], out[i][e + 1], out[i][e + 2], out[i][e + 3]};
+          for (int e = 0; e < 4 * M; e += 4)
+            *reinterpret_cast<f32x4*>(stage + (lane % (64 / M)) * (4 * M) + e) = (f32x4){out[e], out[e + 1], out[e + 2], out[e + 3]};
+        }
+        __syncthreads();
+        const f32x4 v = *reinterpret_cast<const f32x4*>(stage + 4 * lane);
+        const uint32_t unit = (gtid - lane) + (uint32_t)(k * 64 + lane) / M;  // the unit these four floats belong to
+        if (unit < have) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(wave_u + k * 256 + 4 * lane));
+        __syncthreads();
       }
     }
-    solon_phase_align(a.sync, ++nbar, a.spin_limit);
+    solon_phase_align(a.sync, ++nbar, a.spin_limit);  // ends with a block-wide barrier: the slots are free again
   }
   solon_phase_exit(a.sync);
 }
 
+// dynamic LDS of the row-synchronous kernel: the tables, rounded up to 16 bytes, then the store-staging area
+static size_t rows_lds_tables(const solon_plan* plan) {
+  const size_t b = sizeof(double) * (FUSE_BLOCK / 64) * plan->P + sizeof(int) * (plan->P + plan->q + 1) + sizeof(float) * plan->q * plan->m * plan->m;
+  return (b + 15) / 16 * 16;
+}
+static size_t rows_lds(const solon_plan* plan) { return rows_lds_tables(plan) + sizeof(float) * (FUSE_BLOCK / 64) * 256; }
+
 template <int M>
 static int fused_pass(solon_plan* plan, const fuse_args& a0, int grid, hipStream_t st) {
   fuse_args a = a0;
-  const size_t lds = sizeof(double) * (FUSE_BLOCK / 64) * plan->P;
-  hipLaunchKernelGGL((project_recombine_kernel<M>), dim3((unsigned)grid), dim3(FUSE_BLOCK), lds, st, a, a.grp_off, a.order, a.coef);
+  a.stage_off = (int)(rows_lds_tables(plan) / sizeof(float));
+  hipLaunchKernelGGL((project_recombine_kernel<M>), dim3((unsigned)grid), dim3(FUSE_BLOCK), rows_lds(plan), st, a, a.grp_off, a.order, a.coef);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
 
 // Size of the persistent grid of the fused pass for this plan and these buffers, or 0 when the pass does not apply
 // (m not in {1, 2, 4}, unaligned buffers, idle nodes, input too small to pay for it, partial-sum table or LDS too small).
-static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const float* f, const float* u, int64_t nunits) {
+static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const float* f, const float* u, int64_t nunits,
+                      int64_t* per_pass_out) {
   const int want = solon_tuning("fuse", -1);
   if (want == 0 || nunits < 1 || nunits >= ((int64_t)1 << 30)) return 0;
   if (plan->m != 1 && plan->m != 2 && plan->m != 4) return 0;
@@ -179,14 +189,16 @@ static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const
   if ((uintptr_t)R % 16 != 0 || ldr % 4 != 0 || (uintptr_t)f % 16 != 0 || (uintptr_t)u % 16 != 0) return 0;
   const void* k = plan->m == 1 ? (const void*)project_recombine_kernel<1>
                 : plan->m == 2 ? (const void*)project_recombine_kernel<2> : (const void*)project_recombine_kernel<4>;
-  int grid = solon_resident_grid(k, FUSE_BLOCK);
+  int grid = solon_resident_grid(k, FUSE_BLOCK, rows_lds(plan));
   const int cap = solon_tuning("fuse_grid", 0);  // tests: a few blocks that go round many times
   if (cap > 0) grid = std::min(grid, cap);
   if (grid < 1) return 0;
-  const int64_t per_pass = (int64_t)grid * FUSE_BLOCK * FUSE_U;
+  if ((int64_t)grid * FUSE_BLOCK * 16 >= ((int64_t)1 << 32)) return 0;  // 32-bit lane offsets inside a round
+  const int64_t per_pass = (int64_t)grid * FUSE_BLOCK;  // units of a round
   const int64_t npass = (nunits + per_pass - 1) / per_pass;
   if (want < 0 && npass < 8) return 0;  // measured: on small inputs the two separate passes are faster
   if (npass * grid + 64 > SOLON_PROJ_MAX_TILES) return 0;
+  *per_pass_out = per_pass;
   return grid;
 }
 
@@ -207,7 +219,8 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
   hipStream_t st = (hipStream_t)hip_stream;
   const int m = plan->m, P = plan->P;
   const int64_t nunits = (plan->d / m) / 4;  // float4 column units whose chunks all lie below d
-  const int grid = fused_grid(plan, R, ldr, f, u, nunits);
+  int64_t per_pass = 0;
+  const int grid = fused_grid(plan, R, ldr, f, u, nunits, &per_pass);
   int rc;
   if (grid == 0) {  // the two passes of solon_locate + solon_decode
     rc = solon_launch_project(plan, R, ldr, f, st);
@@ -231,10 +244,9 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
     a.R = R; a.ldr = ldr; a.f = f; a.nunits = nunits; a.P = P; a.q = plan->q;
     a.grp_off = plan->dev.grp_off; a.order = plan->dev.spec_order; a.coef = plan->dev.spec_coef;
     a.partials = plan->dev.partials; a.u = u; a.sync = plan->dev.grid_sync;
-    a.spin_limit = solon_tuning("fuse_spin_limit", 0);
+    a.spin_limit = solon_tuning("fuse_spin_limit", 400);
     rc = m == 1 ? fused_pass<1>(plan, a, grid, st) : m == 2 ? fused_pass<2>(plan, a, grid, st) : fused_pass<4>(plan, a, grid, st);
     if (rc != SOLON_OK) return rc;
-    const int64_t per_pass = (int64_t)grid * FUSE_BLOCK * FUSE_U;
     int tiles = (int)((nunits + per_pass - 1) / per_pass) * grid;
     const int64_t done = 4 * nunits;  // columns covered by the pass
     if (done < plan->d_c) {           // at most four whole columns and one partial chunk are left
