@@ -144,6 +144,9 @@ template <typename T> struct phase_units;
 template <> struct phase_units<float> { static constexpr int U = 8; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
 
+// shortest rows of G, in bytes, that the phase-separated kernels are chosen for
+#define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)32 << 20)
+
 // block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within 32 registers
 constexpr int tile_phase_tiles(int sums_per_tile) { return 32 / sums_per_tile > 0 ? 32 / sums_per_tile : 1; }
 
@@ -214,7 +217,9 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
         char* zrow = zph + (int64_t)j * a.ldz * (int64_t)sizeof(float);
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-          if (pace8) solon_pace(t0, step++, pace8);  // step (t, i) of all waves covers one contiguous window of row j
+          // step (t, i) of all waves covers one contiguous window of row j; in the ragged last phase a position none
+          // of whose units lies inside the row takes no slot of the schedule
+          if (pace8 && have[i]) solon_pace(t0, step++, pace8);
           float z[NC];
 #pragma unroll
           for (int c = 0; c < NC; ++c) {
@@ -449,15 +454,16 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
   if (aligned && solon_tuning("encode_force_generic", 0) == 0) {
     if constexpr (LV % M == 0) {  // m divides the load width: one 16-byte load per row and thread
       const int64_t nunits = plan->d / LV;
-      // phase-separated persistent grid when every group keeps the whole chip busy for several phases
+      // Phase-separated persistent grid when the rows are long enough to pay for the alignment points.  Measured at
+      // P = 100 in fp32: rows of 39.7 MB and 44.7 MB (one partly filled phase per group) encode 14 to 18 % faster
+      // than with the flat kernel, rows of 29.3 MB 5 % slower.
       int phase_grid = 0;
       const int want_phase = solon_tuning("encode_phase", -1);
       if (nunits > 0 && want_phase != 0) {
         phase_grid = solon_resident_grid((const void*)encode_phase_kernel<M, T>, 1024);
         const int grid_cap = solon_tuning("encode_phase_grid", 0);  // tests: a few blocks make many phases of a small input
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-        const int64_t per_phase = (int64_t)phase_grid * 1024 * phase_units<T>::U;
-        if (want_phase < 0 && nunits < 2 * per_phase) phase_grid = 0;
+        if (want_phase < 0 && nunits * 16 < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
         if ((int64_t)phase_grid * 1024 * 16 >= ((int64_t)1 << 32)) phase_grid = 0;  // the kernel's 32-bit byte offsets inside a span
       }
       if (phase_grid > 0) {
@@ -488,7 +494,14 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
           (void)hipGetLastError();
         const int grid_cap = solon_tuning("encode_phase_grid", 0);
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-        if (want_phase < 0 && ptiles < 2 * (int64_t)phase_grid * UT) phase_grid = 0;
+        // same rule for the length of the rows; in addition the last phase of a group must not be a nearly empty
+        // one (measured at 1.07 phases per group: 24 % slower than the flat kernel)
+        const int64_t per_phase = (int64_t)phase_grid * UT;
+        if (want_phase < 0 && phase_grid > 0) {
+          const int64_t rest = ptiles % per_phase;
+          if (plan->d * (int64_t)sizeof(T) < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
+          else if (ptiles > per_phase && ptiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
+        }
       }
       if (phase_grid > 0) {
         hipLaunchKernelGGL((encode_tile_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
