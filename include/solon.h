@@ -182,7 +182,8 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
  * "decode_phase_grid" (cap on the persistent grid, 0 = none), "phase_spin_limit", "project_rows", "project_seg",
  * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic",
  * "fuse" (-1 = solon_locate_decode chooses by size, 0 = always two passes, 1 = one pass wherever legal), "fuse_grid",
- * "fuse_sample" (columns of the sample projection behind the guess), "fuse_spin_limit", "project_xcd_map".
+ * "fuse_sample" (columns of the sample projection behind the guess), "fuse_spin_limit", "project_xcd_map",
+ * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced).
  * Unknown keys are stored and ignored. */
 int solon_tune(const char* key, int value);
 
