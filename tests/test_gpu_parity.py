@@ -206,6 +206,45 @@ def test_phase_separated_kernels_equal_flat_kernels_bitwise():
         solon.solon_tune("decode_phase", -1)
 
 
+def test_phase_encoder_with_more_batches_per_group_than_its_table_holds():
+    """A group may own any number of batches; the phase-separated encoder keeps a group's batch indices in a table of
+    64 entries and reads them from memory when there are more."""
+    solon.solon_tune("encode_phase", 1)
+    solon.solon_tune("encode_phase_grid", 3)
+    try:
+        run_case(6, 1, 2, 30_002, B=150, group_of_node=[0] * 6, group_of_batch=[0] * 150, seed=41)
+        gon = [0] * 6 + [1] * 6
+        run_case(12, 1, 2, 20_004, B=70, group_of_node=gon, group_of_batch=[0] * 66 + [1] * 4, dtype="bf16", seed=42)
+    finally:
+        solon.solon_tune("encode_phase", -1)
+        solon.solon_tune("encode_phase_grid", 0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_store_pacing_only_shapes_timing(dtype):
+    """The clock-paced store schedule of the encoder's write phases decides when a store is issued, never what it
+    writes: no pacing, the default rate and a rate slow enough that every step waits give identical bits."""
+    cfg = dict(P=24, d=1_500_008, dtype=dtype, dist="normal", sigma=0.01)
+    plan = solon.Plan(24, 2, 4, cfg["d"], dtype=solon.SOLON_BF16 if dtype == "bf16" else solon.SOLON_F32)
+    G = workloads.make_gradients(cfg, DEV, 43, d=cfg["d"])
+    Z = [torch.zeros((24, plan.d_c), dtype=torch.float32, device=DEV) for _ in range(4)]
+    try:
+        solon.solon_tune("encode_phase", 0)
+        solon.solon_encode(plan, G, Z[0])
+        solon.solon_tune("encode_phase", 1)
+        solon.solon_tune("encode_phase_grid", 5)
+        for z, rate in zip(Z[1:], (0, 7800, 20)):
+            solon.solon_tune("store_pace_gbps", rate)
+            solon.solon_encode(plan, G, z)
+        torch.cuda.synchronize()
+        for z in Z[1:]:
+            assert torch.equal(Z[0], z)
+    finally:
+        solon.solon_tune("encode_phase", -1)
+        solon.solon_tune("encode_phase_grid", 0)
+        solon.solon_tune("store_pace_gbps", 7800)
+
+
 @pytest.mark.parametrize("grid", [2, 0])
 def test_locate_decode_in_one_pass(grid):
     """solon_locate_decode forced onto small inputs (two blocks: several ragged phases): same located set, same
