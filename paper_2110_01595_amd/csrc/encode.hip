@@ -140,9 +140,10 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(enc_args a, int64_t nun
 // instead of their mixture.  For a fixed i the grid covers one contiguous span of every row.  Same arithmetic,
 // same order of additions as encode_vec_kernel.
 // units a thread of the phase-separated kernel keeps in registers: as many as leave eight waves per SIMD resident
+// (40 partial sums; with 48 the kernel would need more than 64 registers)
 template <typename T> struct phase_units;
-template <> struct phase_units<float> { static constexpr int U = 8; };
-template <> struct phase_units<uint16_t> { static constexpr int U = 4; };
+template <> struct phase_units<float> { static constexpr int U = 10; };
+template <> struct phase_units<uint16_t> { static constexpr int U = 5; };
 
 // shortest rows of G, in bytes, that the phase-separated kernels are chosen for
 #define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)32 << 20)

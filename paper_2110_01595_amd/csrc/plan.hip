@@ -69,10 +69,11 @@ int solon_resident_grid(const void* kernel, int threads, size_t dynamic_lds) {
 
 // ---------------------------------------------------------------- store pacing
 uint32_t solon_store_pace8(int64_t step_bytes) {
-  // the rate at which MI355X absorbs ordered writes.  Measured on the encoder at the 124 M-parameter bf16 shape: 4 %
-  // faster at 7.8 TB/s than without pacing, less below (the pace then throttles), and from 8.4 TB/s on the stores are
-  // held back by their own completion rather than the schedule, as without pacing
-  const int gbps = solon_tuning("store_pace_gbps", 7800);
+  // the rate at which MI355X absorbs ordered writes.  Measured on the encoder at the 124 M-parameter bf16 shape: 7 %
+  // faster at 7.8 TB/s than without pacing, 6 % at 7.4 (the pace then throttles), 4 % at 8.0 and 3 % at 8.2 (the stores
+  // are then held back by their own completion rather than the schedule, as without pacing); the default keeps a little
+  // distance from that knee
+  const int gbps = solon_tuning("store_pace_gbps", 7700);
   if (gbps <= 0 || step_bytes <= 0) return 0;
   static std::mutex mu;
   static std::map<int, int> rate;  // constant-rate clock of each device, kHz

@@ -233,7 +233,7 @@ def test_store_pacing_only_shapes_timing(dtype):
         solon.solon_encode(plan, G, Z[0])
         solon.solon_tune("encode_phase", 1)
         solon.solon_tune("encode_phase_grid", 5)
-        for z, rate in zip(Z[1:], (0, 7800, 20)):
+        for z, rate in zip(Z[1:], (0, 7700, 20)):
             solon.solon_tune("store_pace_gbps", rate)
             solon.solon_encode(plan, G, z)
         torch.cuda.synchronize()
@@ -242,7 +242,7 @@ def test_store_pacing_only_shapes_timing(dtype):
     finally:
         solon.solon_tune("encode_phase", -1)
         solon.solon_tune("encode_phase_grid", 0)
-        solon.solon_tune("store_pace_gbps", 7800)
+        solon.solon_tune("store_pace_gbps", 7700)
 
 
 @pytest.mark.parametrize("grid", [2, 0])
