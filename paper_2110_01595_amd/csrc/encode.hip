@@ -284,6 +284,9 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
             int v = tid + 1024 * i;
             if (NVEC % 1024 != 0) v = v < NVEC ? v : NVEC - 1;  // the tile's last vector again (unused)
             load_add<true>(src + v * LV, acc[j][i]);
+            // one load in flight per wave, so that the chip moves through the row together (measured at m = 10: 6 to
+            // 10 % faster than with a tile's loads queued at once; no difference at m = 6 and 8)
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
           }
         }
       }
