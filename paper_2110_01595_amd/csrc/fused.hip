@@ -185,7 +185,7 @@ static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const
   if (want == 0 || nunits < 1 || nunits >= ((int64_t)1 << 30)) return 0;
   if (plan->m != 1 && plan->m != 2 && plan->m != 4) return 0;
   if (plan->n_active != plan->P) return 0;  // the pass projects the rows group by group: idle nodes would be left out
-  if (sizeof(double) * (FUSE_BLOCK / 64) * plan->P > 48 * 1024) return 0;  // one LDS slot per wavefront and node
+  if (rows_lds(plan) > 64 * 1024) return 0;  // one LDS slot per wavefront and node, the tables and the staging area
   if ((uintptr_t)R % 16 != 0 || ldr % 4 != 0 || (uintptr_t)f % 16 != 0 || (uintptr_t)u % 16 != 0) return 0;
   const void* k = plan->m == 1 ? (const void*)project_recombine_kernel<1>
                 : plan->m == 2 ? (const void*)project_recombine_kernel<2> : (const void*)project_recombine_kernel<4>;

@@ -272,6 +272,8 @@ def test_locate_decode_in_one_pass(grid):
         run_case(45, 2, 2, 50_002, attack="noise100", seed=58, fused=True)        # groups of 6 and 7 nodes, m = 2
         run_case(20, 2, 5, 25_003, seed=54, fused=True)                           # m = 5: falls back to the two passes
         run_case(15, 1, 2, 40_002, pad=1, seed=55, fused=True)                    # unaligned rows: falls back
+        run_case(448, 5, 4, 4_000, attack="mix", seed=59, fused=True, check_bruteforce=False)   # LDS slots for 448 nodes exceed 64 KB: falls back
+        run_case(300, 5, 4, 6_000, attack="mix", seed=60, fused=True, check_bruteforce=False)   # 300 nodes still fit
     finally:
         solon.solon_tune("fuse", -1)
         solon.solon_tune("fuse_grid", 0)
