@@ -66,10 +66,6 @@ __device__ __forceinline__ void add_raw(const u32x4 v, float* acc, uint16_t) {
   acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xffff0000u);
 }
 
-// word 3 of a raw buffer descriptor on gfx9 (32-bit data format, no swizzle) and the non-temporal bit of the cache policy
-#define SOLON_BUFFER_WORD3 0x00020000
-#define SOLON_BUFFER_NT 2
-
 template <int NC, bool NT>
 __device__ __forceinline__ void store_chunks(float* dst, const float* z) {
   if constexpr (NC % 4 == 0) {

@@ -49,9 +49,6 @@ struct fuse_args {
 // with six to eight rows in flight per lane and half the waves was 9 % slower).  Rows are read through buffer
 // descriptors (wave-uniform base, 32-bit lane offset, hardware range check: past the end of the row a load returns
 // zeros and f is zero there too).  The three small tables are copied to LDS once.
-#define ROWS_WORD3 0x00020000  // word 3 of a raw buffer descriptor on gfx9: 32-bit data format, no swizzle
-#define ROWS_NT 2              // non-temporal bit of the cache policy
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int M>
@@ -81,7 +78,7 @@ __global__ __launch_bounds__(FUSE_BLOCK, 8) void project_recombine_kernel(fuse_a
     const int64_t tl = (int64_t)ph * gridDim.x + blockIdx.x;
     double f0, f1, f2, f3;
     {
-      const __amdgpu_buffer_rsrc_t fd = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.f) + ubase * 4, 0, have * 16u, ROWS_WORD3);
+      const __amdgpu_buffer_rsrc_t fd = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.f) + ubase * 4, 0, have * 16u, SOLON_BUFFER_WORD3);
       const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(fd, gtid * 16u, 0, 0);
       f0 = __uint_as_float(v.x); f1 = __uint_as_float(v.y); f2 = __uint_as_float(v.z); f3 = __uint_as_float(v.w);
     }
@@ -93,8 +90,8 @@ __global__ __launch_bounds__(FUSE_BLOCK, 8) void project_recombine_kernel(fuse_a
     // row is issued as soon as the current row's has arrived and before its arithmetic, so that a wave has one load
     // in flight all the time rather than none while it reduces.
     int node = __builtin_amdgcn_readfirstlane(s_order[0]);
-    u32x4 ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, ROWS_WORD3),
-                                                        gtid * 16u, 0, ROWS_NT);
+    u32x4 ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, SOLON_BUFFER_WORD3),
+                                                        gtid * 16u, 0, SOLON_BUFFER_NT);
     int t = 0;
     for (int g = 0; g < a.q; ++g) {
       const int n0 = __builtin_amdgcn_readfirstlane(s_off[g]), n1 = __builtin_amdgcn_readfirstlane(s_off[g + 1]);
@@ -104,8 +101,8 @@ __global__ __launch_bounds__(FUSE_BLOCK, 8) void project_recombine_kernel(fuse_a
         const int cur = node;
         if (t + 1 < a.P) {
           node = __builtin_amdgcn_readfirstlane(s_order[t + 1]);
-          ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, ROWS_WORD3),
-                                                        gtid * 16u, 0, ROWS_NT);
+          ahead = __builtin_amdgcn_raw_buffer_load_b128(__builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * a.ldr, 0, have * 16u, SOLON_BUFFER_WORD3),
+                                                        gtid * 16u, 0, SOLON_BUFFER_NT);
         }
         __builtin_amdgcn_sched_barrier(0);
         const float v[4] = {__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z), __uint_as_float(raw.w)};

@@ -11,6 +11,10 @@
 #define SOLON_MAX_M 16          // largest compression ratio with a compiled kernel
 #define SOLON_PROJ_ROWS 32      // most rows of R one projection block accumulates at once
 #define SOLON_PROJ_MAX_TILES 16384
+// raw buffer descriptors (wave-uniform base and length, 32-bit lane offsets, hardware range check): word 3 on gfx9
+// (32-bit data format, no swizzle) and the non-temporal bit of a buffer instruction's cache policy
+#define SOLON_BUFFER_WORD3 0x00020000
+#define SOLON_BUFFER_NT 2
 #define SOLON_SYNC_WORDS 512     // 8 counters 128 bytes apart, one grid-wide counter, one exit counter
 
 // Device-side tables of a plan; every pointer points into the plan's single workspace allocation.
