@@ -464,6 +464,35 @@ def test_linearity_of_encode_and_decode():
     assert so.rel_l2(Z3.cpu().numpy(), (0.5 * Z1 - 2.0 * Z2).cpu().numpy()) <= 1e-6
 
 
+def test_randomised_rounds_through_the_persistent_kernels():
+    """Random shapes, element types, grid sizes and attacks with every persistent kernel forced on (phase-separated
+    encoders and recombination, the one-pass locate + decode): few blocks make many ragged phases and rounds, a full
+    grid leaves most positions of a phase empty.  Every round is compared with the oracle step by step."""
+    rng = np.random.default_rng(77)
+    shapes = [(7, 1, 1), (15, 1, 2), (31, 2, 2), (63, 3, 4), (100, 5, 4), (24, 2, 4), (45, 2, 3), (40, 3, 10), (24, 2, 8), (12, 1, 6)]
+    attacks = ["flip10", "noise100", "mix", "alie", "collude50"]
+    for knob in ("encode_phase", "decode_phase", "fuse"):
+        solon.solon_tune(knob, 1)
+    solon.solon_tune("fuse_sample", 512)
+    try:
+        for case in range(36):
+            P, s, m = shapes[case % len(shapes)]
+            grid = int(rng.choice([1, 2, 3, 5, 0]))
+            for knob in ("encode_phase_grid", "decode_phase_grid", "fuse_grid"):
+                solon.solon_tune(knob, grid)
+            lo, hi = (3_000, 60_000) if grid else (200_000, 900_000)
+            d = int(rng.integers(lo, hi))
+            run_case(P, s, m, d, dtype=str(rng.choice(["f32", "bf16"])), attack=str(rng.choice(attacks)),
+                     n_byz=int(rng.integers(0, s + 1)), seed=7000 + case, fused=bool(rng.integers(0, 2)),
+                     u_tol=5e-3 if m >= 8 else 1e-4)
+    finally:
+        for knob in ("encode_phase", "decode_phase", "fuse"):
+            solon.solon_tune(knob, -1)
+        for knob in ("encode_phase_grid", "decode_phase_grid", "fuse_grid"):
+            solon.solon_tune(knob, 0)
+        solon.solon_tune("fuse_sample", 1 << 17)
+
+
 def test_randomised_locate_against_oracle():
     """Many small random instances: shapes, per-group numbers of corrupted nodes (0..s), attack kinds and strengths.
     The located set must equal the oracle's on the same R; it must equal the planted set whenever every planted
