@@ -144,8 +144,9 @@ template <> struct phase_units<uint16_t> { static constexpr int U = 5; };
 // shortest rows of G, in bytes, that the phase-separated kernels are chosen for
 #define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)32 << 20)
 
-// block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within 32 registers
-constexpr int tile_phase_tiles(int sums_per_tile) { return 32 / sums_per_tile > 0 ? 32 / sums_per_tile : 1; }
+// block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within `budget`
+// registers.  32 gives the faster code; 40 is used where it saves a phase per group.
+constexpr int tile_phase_tiles(int sums_per_tile, int budget) { return budget / sums_per_tile > 0 ? budget / sums_per_tile : 1; }
 
 template <int M, typename T>
 __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64_t nunits, int q, uint32_t* sync, int spin_limit, uint32_t pace8, ENC_TABLE_PARAMS) {
@@ -244,12 +245,12 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
 // registers (coalesced 16-byte loads).  Write phase: tile by tile the sums pass through LDS, each thread picks up
 // the m coefficients of its own chunk and writes one message element per node.  Same order of additions as
 // encode_tile_kernel.
-template <int M, typename T>
+template <int M, typename T, int BUDGET>
 __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, int64_t ntiles, int q, uint32_t* sync, int spin_limit, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NVEC = 1024 * M / LV;           // 16-byte vectors per row and block-tile (1024 m is a multiple of LV)
   constexpr int NI = (NVEC + 1023) / 1024;      // vectors per thread and block-tile
-  constexpr int UT = tile_phase_tiles(NI * LV); // block-tiles per block and phase
+  constexpr int UT = tile_phase_tiles(NI * LV, BUDGET);  // block-tiles per block and phase
   extern __shared__ float ybar[];               // [1024 * M]
   const int tid = threadIdx.x;
   const int64_t per_phase = (int64_t)gridDim.x * UT;
@@ -484,28 +485,41 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       const int64_t ptiles = plan->d / (1024 * M);  // block-tiles of 1024 chunks that lie entirely below d
       const int want_phase = solon_tuning("encode_phase", -1);
       int phase_grid = 0;
-      constexpr int UT = tile_phase_tiles((1024 * M / LV + 1023) / 1024 * LV);
+      constexpr int SUMS = (1024 * M / LV + 1023) / 1024 * LV;  // partial sums per thread and block-tile
+      constexpr int UT32 = tile_phase_tiles(SUMS, 32), UT40 = tile_phase_tiles(SUMS, 40);
       const size_t lds = sizeof(float) * 1024 * M;
+      bool wide = false;  // the 40-register version
       if (ptiles > 0 && want_phase != 0) {
-        const void* k = (const void*)encode_tile_phase_kernel<M, T>;
-        if (lds <= 64 * 1024 || hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess)
-          phase_grid = solon_resident_grid(k, 1024, lds);
+        const void* k32 = (const void*)encode_tile_phase_kernel<M, T, 32>;
+        const void* k40 = (const void*)encode_tile_phase_kernel<M, T, 40>;
+        if (lds <= 64 * 1024 || (hipFuncSetAttribute(k32, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess &&
+                                 hipFuncSetAttribute(k40, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) == hipSuccess))
+          phase_grid = std::min(solon_resident_grid(k32, 1024, lds), solon_resident_grid(k40, 1024, lds));
         else
           (void)hipGetLastError();
         const int grid_cap = solon_tuning("encode_phase_grid", 0);
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-        // same rule for the length of the rows; in addition the last phase of a group must not be a nearly empty
-        // one (measured at 1.07 phases per group: 24 % slower than the flat kernel)
-        const int64_t per_phase = (int64_t)phase_grid * UT;
-        if (want_phase < 0 && phase_grid > 0) {
-          const int64_t rest = ptiles % per_phase;
-          if (plan->d * (int64_t)sizeof(T) < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
-          else if (ptiles > per_phase && ptiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
+        if (phase_grid > 0) {
+          const int64_t n32 = (ptiles + (int64_t)phase_grid * UT32 - 1) / ((int64_t)phase_grid * UT32);
+          const int64_t n40 = (ptiles + (int64_t)phase_grid * UT40 - 1) / ((int64_t)phase_grid * UT40);
+          wide = UT40 > UT32 && n40 < n32;
+          // same rule for the length of the rows as above; in addition the last phase of a group must not be a nearly
+          // empty one (measured at 1.07 phases per group: 24 % slower than the flat kernel)
+          const int64_t per_phase = (int64_t)phase_grid * (wide ? UT40 : UT32);
+          if (want_phase < 0) {
+            const int64_t rest = ptiles % per_phase;
+            if (plan->d * (int64_t)sizeof(T) < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
+            else if (ptiles > per_phase && ptiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
+          }
         }
       }
       if (phase_grid > 0) {
-        hipLaunchKernelGGL((encode_tile_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
-                           plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
+        if (wide)
+          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 40>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
+                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
+        else
+          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 32>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
+                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = ptiles * 1024;
       }
