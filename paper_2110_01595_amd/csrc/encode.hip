@@ -141,8 +141,14 @@ template <typename T> struct phase_units;
 template <> struct phase_units<float> { static constexpr int U = 10; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 5; };
 
-// shortest rows of G, in bytes, that the phase-separated kernels are chosen for
-#define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)32 << 20)
+// The phase-separated kernels are chosen for rows of G of at least this many bytes whose groups read at least that
+// many bytes (measured, P = 100: rows of 29 MB in groups of 14 encode 6 to 14 % faster than with the flat kernels,
+// rows of 24 MB equally fast; P = 15: 45 MB rows in groups of 5, 224 MB, 7 % slower)
+#define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)24 << 20)
+#define SOLON_PHASE_MIN_GROUP_BYTES ((int64_t)320 << 20)
+static bool phase_pays(const solon_plan* plan, int64_t row_bytes) {
+  return row_bytes >= SOLON_PHASE_MIN_ROW_BYTES && row_bytes * (plan->B / plan->q) >= SOLON_PHASE_MIN_GROUP_BYTES;
+}
 
 // block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within `budget`
 // registers.  32 gives the faster code; 40 is used where it saves a phase per group.
@@ -201,8 +207,10 @@ __global__ __launch_bounds__(1024, 8) void encode_phase_kernel(enc_args a, int64
         // reads from U spans of the row at once instead of moving through them in step
 #pragma unroll
         for (int i = 0; i < U; ++i) {
-          const __amdgpu_buffer_rsrc_t piece = __builtin_amdgcn_make_buffer_rsrc(src + (int64_t)i * span * 16, 0, have[i] * 16u, SOLON_BUFFER_WORD3);
-          add_raw(__builtin_amdgcn_raw_buffer_load_b128(piece, gtid * 16u, 0, SOLON_BUFFER_NT), acc[i], T());
+          if (have[i] != 0) {  // wave-uniform: an empty position of the ragged last phase costs no round trip
+            const __amdgpu_buffer_rsrc_t piece = __builtin_amdgcn_make_buffer_rsrc(src + (int64_t)i * span * 16, 0, have[i] * 16u, SOLON_BUFFER_WORD3);
+            add_raw(__builtin_amdgcn_raw_buffer_load_b128(piece, gtid * 16u, 0, SOLON_BUFFER_NT), acc[i], T());
+          }
         }
       }
       solon_phase_align(sync, ++nbar, spin_limit);
@@ -273,17 +281,18 @@ __global__ __launch_bounds__(1024, 8) void encode_tile_phase_kernel(enc_args a, 
         const T* row = static_cast<const T*>(a.G) + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
         for (int j = 0; j < UT; ++j) {
-          int64_t tile = t0 + (int64_t)j * gridDim.x;
-          tile = tile < ntiles ? tile : ntiles - 1;  // past the end: the last tile again (in bounds, result unused)
-          const T* src = row + tile * (1024 * M);
+          const int64_t tile = t0 + (int64_t)j * gridDim.x;
+          if (tile < ntiles) {  // block-uniform: a slot past the end of the ragged last phase costs nothing
+            const T* src = row + tile * (1024 * M);
 #pragma unroll
-          for (int i = 0; i < NI; ++i) {
-            int v = tid + 1024 * i;
-            if (NVEC % 1024 != 0) v = v < NVEC ? v : NVEC - 1;  // the tile's last vector again (unused)
-            load_add<true>(src + v * LV, acc[j][i]);
-            // one load in flight per wave, so that the chip moves through the row together (measured at m = 10: 6 to
-            // 10 % faster than with a tile's loads queued at once; no difference at m = 6 and 8)
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            for (int i = 0; i < NI; ++i) {
+              int v = tid + 1024 * i;
+              if (NVEC % 1024 != 0) v = v < NVEC ? v : NVEC - 1;  // the tile's last vector again (unused)
+              load_add<true>(src + v * LV, acc[j][i]);
+              // one load in flight per wave, so that the chip moves through the row together (measured at m = 10: 6 to
+              // 10 % faster than with a tile's loads queued at once; no difference at m = 6 and 8)
+              asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
           }
         }
       }
@@ -455,16 +464,14 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
   if (aligned && solon_tuning("encode_force_generic", 0) == 0) {
     if constexpr (LV % M == 0) {  // m divides the load width: one 16-byte load per row and thread
       const int64_t nunits = plan->d / LV;
-      // Phase-separated persistent grid when the rows are long enough to pay for the alignment points.  Measured at
-      // P = 100 in fp32: rows of 39.7 MB and 44.7 MB (one partly filled phase per group) encode 14 to 18 % faster
-      // than with the flat kernel, rows of 29.3 MB 5 % slower.
+      // phase-separated persistent grid when the rows are long enough to pay for the alignment points
       int phase_grid = 0;
       const int want_phase = solon_tuning("encode_phase", -1);
       if (nunits > 0 && want_phase != 0) {
         phase_grid = solon_resident_grid((const void*)encode_phase_kernel<M, T>, 1024);
         const int grid_cap = solon_tuning("encode_phase_grid", 0);  // tests: a few blocks make many phases of a small input
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-        if (want_phase < 0 && nunits * 16 < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
+        if (want_phase < 0 && !phase_pays(plan, nunits * 16)) phase_grid = 0;
         if ((int64_t)phase_grid * 1024 * 16 >= ((int64_t)1 << 32)) phase_grid = 0;  // the kernel's 32-bit byte offsets inside a span
       }
       if (phase_grid > 0) {
@@ -508,7 +515,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
           const int64_t per_phase = (int64_t)phase_grid * (wide ? UT40 : UT32);
           if (want_phase < 0) {
             const int64_t rest = ptiles % per_phase;
-            if (plan->d * (int64_t)sizeof(T) < SOLON_PHASE_MIN_ROW_BYTES) phase_grid = 0;
+            if (!phase_pays(plan, plan->d * (int64_t)sizeof(T))) phase_grid = 0;
             else if (ptiles > per_phase && ptiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
           }
         }
