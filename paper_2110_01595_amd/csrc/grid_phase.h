@@ -47,7 +47,7 @@ __device__ __forceinline__ void solon_phase_align(uint32_t* sync, uint32_t nbar,
 __device__ __forceinline__ void solon_pace(unsigned long long t0, uint32_t step, uint32_t pace8) {
   const unsigned long long due = t0 + (((unsigned long long)step * pace8) >> 3);
   int n = 0;
-  while (wall_clock64() < due && n < 256) {
+  while ((unsigned long long)wall_clock64() < due && n < 256) {
     __builtin_amdgcn_s_sleep(1);
     ++n;
   }
