@@ -368,7 +368,7 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
 // loads (that part does not depend on m), parked in LDS, and then each thread picks up the m coefficients of its
 // own chunk and writes one message element per node (coalesced 4-byte stores).
 template <int M, typename T, bool NT>
-__global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, ENC_TABLE_PARAMS) {
+__global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t tile0, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NVEC = 256 * M / LV;          // 16-byte vectors per row and tile
   constexpr int NI = (NVEC + 255) / 256;      // vectors per thread
@@ -376,7 +376,7 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, ENC_TABLE_
   const int g = blockIdx.y, tid = threadIdx.x;
   const int b0 = bat_off[g], b1 = bat_off[g + 1];
   const int n0 = grp_off[g], n1 = grp_off[g + 1];
-  const int64_t tile = blockIdx.x;
+  const int64_t tile = tile0 + blockIdx.x;
   const T* base = static_cast<const T*>(a.G) + tile * (256 * M);
   float acc[NI][LV];
 #pragma unroll
@@ -495,7 +495,8 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       constexpr int SUMS = (1024 * M / LV + 1023) / 1024 * LV;  // partial sums per thread and block-tile
       constexpr int UT32 = tile_phase_tiles(SUMS, 32), UT40 = tile_phase_tiles(SUMS, 40);
       const size_t lds = sizeof(float) * 1024 * M;
-      bool wide = false;  // the 40-register version
+      bool wide = false;            // the 40-register version
+      int64_t phase_tiles = ptiles;  // block-tiles given to the phase-separated kernel
       if (ptiles > 0 && want_phase != 0) {
         const void* k32 = (const void*)encode_tile_phase_kernel<M, T, 32>;
         const void* k40 = (const void*)encode_tile_phase_kernel<M, T, 40>;
@@ -507,36 +508,39 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         const int grid_cap = solon_tuning("encode_phase_grid", 0);
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
         if (phase_grid > 0) {
-          const int64_t n32 = (ptiles + (int64_t)phase_grid * UT32 - 1) / ((int64_t)phase_grid * UT32);
-          const int64_t n40 = (ptiles + (int64_t)phase_grid * UT40 - 1) / ((int64_t)phase_grid * UT40);
+          // a last position that only a few blocks would work on (the others idle through it) goes to the flat kernel
+          if (ptiles >= phase_grid && (ptiles % phase_grid) * 8 < ptiles) phase_tiles = ptiles - ptiles % phase_grid;
+          const int64_t n32 = (phase_tiles + (int64_t)phase_grid * UT32 - 1) / ((int64_t)phase_grid * UT32);
+          const int64_t n40 = (phase_tiles + (int64_t)phase_grid * UT40 - 1) / ((int64_t)phase_grid * UT40);
           wide = UT40 > UT32 && n40 < n32;
           // same rule for the length of the rows as above; in addition the last phase of a group must not be a nearly
           // empty one (measured at 1.07 phases per group: 24 % slower than the flat kernel)
           const int64_t per_phase = (int64_t)phase_grid * (wide ? UT40 : UT32);
           if (want_phase < 0) {
-            const int64_t rest = ptiles % per_phase;
+            const int64_t rest = phase_tiles % per_phase;
             if (!phase_pays(plan, plan->d * (int64_t)sizeof(T))) phase_grid = 0;
-            else if (ptiles > per_phase && ptiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
+            else if (phase_tiles > per_phase && phase_tiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
           }
         }
       }
       if (phase_grid > 0) {
         if (wide)
-          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 40>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
+          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 40>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, phase_tiles, q,
                              plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
         else
-          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 32>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, ptiles, q,
+          hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 32>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, phase_tiles, q,
                              plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
-        done_chunks = ptiles * 1024;
+        done_chunks = phase_tiles * 1024;
       }
-      const int64_t ntiles = phase_grid > 0 ? 0 : plan->d / (256 * M);
+      const int64_t tile0 = phase_grid > 0 ? 4 * phase_tiles : 0;  // flat tiles of 256 chunks from here on
+      const int64_t ntiles = plan->d / (256 * M) - tile0;
       if (ntiles > 0) {
         dim3 grid((unsigned)ntiles, (unsigned)q);
-        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, ENC_TABLE_ARGS(a));
-        else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a, ENC_TABLE_ARGS(a));
+        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
+        else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
-        done_chunks = ntiles * 256;
+        done_chunks = (tile0 + ntiles) * 256;
       }
     }
   }
