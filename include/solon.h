@@ -183,7 +183,9 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
  * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic",
  * "fuse" (-1 = solon_locate_decode chooses by size, 0 = always two passes, 1 = one pass wherever legal), "fuse_grid",
  * "fuse_sample" (columns of the sample projection behind the guess), "fuse_spin_limit", "project_xcd_map",
- * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced).
+ * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced),
+ * "majority_rows" (-1 = solon_decode_majority chooses by size, 0 = flat kernels, 1 = the persistent kernel wherever legal),
+ * "majority_rows_grid".
  * Unknown keys are stored and ignored. */
 int solon_tune(const char* key, int value);
 

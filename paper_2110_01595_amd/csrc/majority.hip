@@ -3,6 +3,7 @@
 // the group's nodes, found with the Boyer-Moore streaming majority vote (the paper's appendix on the repetition
 // code and its "Streaming Majority Vote" listing), then the sum over groups.  Nodes that differ from the majority
 // anywhere are reported as Byzantine.  One pass over R, one pass over u; no projection, no locator system.
+#include "grid_phase.h"
 #include "solon_internal.h"
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -128,6 +129,82 @@ __global__ __launch_bounds__(256) void majority_reg_kernel(const float* __restri
   __builtin_nontemporal_store(total, reinterpret_cast<f32x4*>(u + c0));
 }
 
+
+// Row-synchronous version for long rows and groups of at most NMAX nodes (16-byte aligned rows).  A persistent grid;
+// each round a thread takes one float4 column unit through all groups, loading a group's rows one at a time (a single
+// load in flight per wave, so that the whole chip reads one span of one row together, the access order HBM serves
+// fastest) into registers, then votes and confirms as above; u is stored 16 bytes per lane without gaps, and the block
+// waits for the whole chip (bounded) before the next round.  Rows are read through buffer descriptors (wave-uniform
+// base, 32-bit lane offset, hardware range check: past the end of the rows every load returns zeros, which agree).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int NMAX>
+__global__ __launch_bounds__(1024, 8) void majority_rows_kernel(const float* __restrict__ R, int64_t ldr, int q, int P,
+                                                                 const int32_t* __restrict__ grp_off, const int32_t* __restrict__ grp_nodes,
+                                                                 float* __restrict__ u, int64_t nunits, int32_t* __restrict__ vmask,
+                                                                 int32_t* __restrict__ status, uint32_t* sync, int spin_limit) {
+  extern __shared__ int s_tab[];  // P node indices, then q + 1 group offsets
+  int* s_nodes = s_tab;
+  int* s_off = s_tab + P;
+  const int tid = threadIdx.x;
+  for (int n = tid; n < grp_off[q]; n += 1024) s_nodes[n] = grp_nodes[n];
+  for (int n = tid; n <= q; n += 1024) s_off[n] = grp_off[n];
+  __syncthreads();
+  const uint32_t span = gridDim.x * 1024u;  // the launcher keeps span * 16 below 2^32
+  const uint32_t gtid = blockIdx.x * 1024u + tid;
+  const int nround = (int)((nunits + span - 1) / span);
+  uint32_t nbar = 0;
+  for (int ph = 0; ph < nround; ++ph) {
+    const int64_t ubase = (int64_t)ph * span;
+    const int64_t left = nunits - ubase;
+    const uint32_t have = left < (int64_t)span ? (uint32_t)left : span;  // units of the round inside the rows, at least one
+    float* rph = const_cast<float*>(R) + ubase * 4;
+    f32x4 total = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int g = 0; g < q; ++g) {
+      const int n0 = __builtin_amdgcn_readfirstlane(s_off[g]), n = __builtin_amdgcn_readfirstlane(s_off[g + 1]) - n0;
+      f32x4 v[NMAX];
+#pragma unroll
+      for (int t = 0; t < NMAX; ++t) {
+        if (t < n) {
+          const int node = __builtin_amdgcn_readfirstlane(s_nodes[n0 + t]);
+          const __amdgpu_buffer_rsrc_t row = __builtin_amdgcn_make_buffer_rsrc(rph + (int64_t)node * ldr, 0, have * 16u, SOLON_BUFFER_WORD3);
+          const u32x4 raw = __builtin_amdgcn_raw_buffer_load_b128(row, gtid * 16u, 0, SOLON_BUFFER_NT);
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          v[t] = (f32x4){__uint_as_float(raw.x), __uint_as_float(raw.y), __uint_as_float(raw.z), __uint_as_float(raw.w)};
+        }
+      }
+      float cand[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      int count[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < NMAX; ++t) {
+        if (t < n) {
+          const float x[4] = {v[t].x, v[t].y, v[t].z, v[t].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const bool fresh = count[e] == 0, same = cand[e] == x[e];
+            cand[e] = fresh ? x[e] : cand[e];
+            count[e] = fresh ? 1 : (same ? count[e] + 1 : count[e] - 1);
+          }
+        }
+      }
+      int agree[4] = {0, 0, 0, 0};
+#pragma unroll
+      for (int t = 0; t < NMAX; ++t) {
+        if (t < n) {
+          const bool s0 = v[t].x == cand[0], s1 = v[t].y == cand[1], s2 = v[t].z == cand[2], s3 = v[t].w == cand[3];
+          agree[0] += s0; agree[1] += s1; agree[2] += s2; agree[3] += s3;
+          if (!(s0 && s1 && s2 && s3)) vmask[s_nodes[n0 + t]] = 1;  // every writer stores the same value
+        }
+      }
+      if (2 * min(min(agree[0], agree[1]), min(agree[2], agree[3])) <= n) status[g] = SOLON_E_DECODE;
+      total += (f32x4){cand[0], cand[1], cand[2], cand[3]};
+    }
+    if (gtid < have) __builtin_nontemporal_store(total, reinterpret_cast<f32x4*>(u + (ubase + gtid) * 4));
+    solon_phase_align(sync, ++nbar, spin_limit);
+  }
+  solon_phase_exit(sync);
+}
+
 extern "C" int solon_decode_majority(solon_plan* plan, const float* R, int64_t ldr, float* u, int32_t* byz_idx, int32_t* n_byz,
                                      void* hip_stream) {
   if (!plan || !R || !u) {
@@ -154,7 +231,24 @@ extern "C" int solon_decode_majority(solon_plan* plan, const float* R, int64_t l
   if (vec) {
     const int64_t units = plan->d / 4;
     const dim3 grid((unsigned)((units + 255) / 256));
-    if (plan->max_group <= 16)  // (an 8-node instance compiled to 234 registers per lane and ran slower than this one)
+    // long rows in groups of at most nine nodes: the persistent row-synchronous kernel
+    int rows_grid = 0;
+    const size_t rlds = sizeof(int) * (plan->P + plan->q + 1);
+    const int want_rows = solon_tuning("majority_rows", -1);
+    // (nine rows of four values are what fits eight waves per SIMD; a sixteen-row version at four waves per SIMD
+    // ran 26 % slower than the flat kernel below)
+    if (plan->max_group <= 9 && want_rows != 0 && rlds <= 64 * 1024) {
+      rows_grid = solon_resident_grid((const void*)majority_rows_kernel<9>, 1024, rlds);
+      const int grid_cap = solon_tuning("majority_rows_grid", 0);  // tests: a few blocks that go round many times
+      if (grid_cap > 0) rows_grid = std::min(rows_grid, grid_cap);
+      if ((int64_t)rows_grid * 1024 * 16 >= ((int64_t)1 << 32)) rows_grid = 0;
+      if (want_rows < 0 && units < 4 * (int64_t)rows_grid * 1024) rows_grid = 0;
+    }
+    if (rows_grid > 0)
+      hipLaunchKernelGGL(majority_rows_kernel<9>, dim3((unsigned)rows_grid), dim3(1024), rlds, st, R, ldr, plan->q, plan->P, plan->dev.grp_off,
+                         plan->dev.grp_nodes, u, units, plan->dev.vmask, plan->dev.status, plan->dev.grid_sync,
+                         solon_tuning("phase_spin_limit", 400));
+    else if (plan->max_group <= 16)  // (an 8-node instance compiled to 234 registers per lane and ran slower than this one)
       hipLaunchKernelGGL(majority_reg_kernel<16>, grid, dim3(256), 0, st, R, ldr, plan->q, plan->dev.grp_off, plan->dev.grp_nodes, u,
                          plan->d, plan->dev.vmask, plan->dev.status);
     else

@@ -80,6 +80,20 @@ def test_gpu_majority_matches_oracle_and_general_path(P, s, d, pad):
     V = solon.solon_decode_majority(plan, R, u[:d])
     assert solon.solon_decode_status(plan) == solon.SOLON_OK
     assert bool((u[d:] == 5.0).all())
+    # the persistent row-synchronous kernel forced onto this small input (two blocks: several ragged rounds; the full
+    # grid: most lanes past the end of the rows) gives the same bits and the same set wherever it applies
+    for grid in (2, 0):
+        solon.solon_tune("majority_rows", 1)
+        solon.solon_tune("majority_rows_grid", grid)
+        try:
+            u_rows = torch.full((d + 3,), 5.0, dtype=torch.float32, device=dev)
+            V_rows = solon.solon_decode_majority(plan, R, u_rows[:d])
+            assert solon.solon_decode_status(plan) == solon.SOLON_OK
+        finally:
+            solon.solon_tune("majority_rows", -1)
+            solon.solon_tune("majority_rows_grid", 0)
+        assert V_rows == V
+        assert torch.equal(u_rows, u)
     u_ref, V_ref = so.decode_majority(oplan, R.cpu().numpy(), d)
     assert V == V_ref == byz
     assert so.rel_l2(u[:d].cpu().numpy(), u_ref) <= 1e-6
