@@ -194,6 +194,13 @@ struct solve_smem {
   int piv[64];
 };
 
+// Value of `v` in lane `src` (src must be wave-uniform): two scalar broadcasts, no LDS.
+__device__ __forceinline__ double lane_bcast(double v, int src) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+  return __hiloint2double(hi, lo);
+}
+
 // Least squares min ||A x - b|| by Householder QR without pivoting; b is column nc of S.A.  A column whose
 // remaining part is (numerically) zero is dependent on earlier ones: its unknown is set to zero, which picks
 // one of the system's solutions (any solution locates the same nodes, Lemma l9 case (ii)).
@@ -256,13 +263,6 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
   __syncthreads();
 }
 
-// Value of `v` in lane `src` (src must be wave-uniform): two scalar broadcasts, no LDS.
-__device__ __forceinline__ double lane_bcast(double v, int src) {
-  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
-  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
-  return __hiloint2double(hi, lo);
-}
-
 // Number of lanes (among `active`, all below `n`) whose value precedes this lane's in the total order (value, lane).
 __device__ int wave_rank(double v, bool active, int n, int lane) {
   const unsigned long long mask = __ballot(active);
@@ -272,6 +272,32 @@ __device__ int wave_rank(double v, bool active, int n, int lane) {
     if ((mask >> j) & 1ull) rank += (o < v || (o == v && j < lane)) ? 1 : 0;
   }
   return rank;
+}
+
+// Lane holding the largest `key` among the lanes with `valid` set, the lowest such lane on ties (-1 if there is none):
+// the reduction pattern of wave_sum_lane63 on (key, lane) pairs.  A lane outside a step's row mask, or without a
+// source lane, meets its own pair again, which changes nothing.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void dpp_best(double& key, int& idx) {
+  const int lo = __builtin_amdgcn_update_dpp(__double2loint(key), __double2loint(key), CTRL, ROW_MASK, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(__double2hiint(key), __double2hiint(key), CTRL, ROW_MASK, 0xF, false);
+  const int oi = __builtin_amdgcn_update_dpp(idx, idx, CTRL, ROW_MASK, 0xF, false);
+  const double ok = __hiloint2double(hi, lo);
+  const bool take = ok > key || (ok == key && oi < idx);
+  key = take ? ok : key;
+  idx = take ? oi : idx;
+}
+__device__ int wave_argmax(double key, bool valid, int lane) {
+  double k = valid ? key : -1.0;  // keys are products of distances: never negative
+  int i = valid ? lane : 64;
+  dpp_best<0xB1, 0xF>(k, i);   // quad_perm [1,0,3,2]
+  dpp_best<0x4E, 0xF>(k, i);   // quad_perm [2,3,0,1]
+  dpp_best<0x141, 0xF>(k, i);  // row_half_mirror
+  dpp_best<0x140, 0xF>(k, i);  // row_mirror
+  dpp_best<0x142, 0xA>(k, i);  // row_bcast:15 into rows 1 and 3
+  dpp_best<0x143, 0xC>(k, i);  // row_bcast:31 into rows 2 and 3
+  const int best = __builtin_amdgcn_readlane(i, 63);
+  return best < 64 ? best : -1;
 }
 
 // Sum over the wavefront, identical bits in every lane.
@@ -438,16 +464,9 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
     bool taken = false;
     double prod = fabs(wi);  // first pick: largest |w|
     for (int t = 0; t < m; ++t) {
-      const bool avail = honest && !taken;
-      const int rk = wave_rank(avail ? -prod : 0.0, avail, n, lane);  // rank 0 = largest product, lowest lane on ties
-      if (avail && rk == 0) {
-        S.med[0] = wi;
-        taken = true;
-      }
-      __syncthreads();
-      const double wsel = S.med[0];
-      __syncthreads();
-      const double dist = fabs(wi - wsel);
+      const int sel = wave_argmax(prod, honest && !taken, lane);  // largest product, lowest lane on ties; nh >= m: never -1
+      if (lane == sel) taken = true;
+      const double dist = fabs(wi - lane_bcast(wi, sel));
       prod = (t == 0) ? dist : prod * dist;
     }
     const unsigned long long taken_mask = __ballot(taken);
