@@ -247,18 +247,18 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
     __syncthreads();
     ++row;
   }
-  if (lane == 0) {
-    for (int k = nc - 1; k >= 0; --k) {
-      const int r = S.piv[k];
-      if (r < 0) {
-        S.x[k] = 0.0;
-        continue;
-      }
-      double acc = S.A[r][nc];
-#pragma unroll 4
-      for (int j = k + 1; j < nc; ++j) acc = fma(-S.A[r][j], S.x[j], acc);
-      S.x[k] = acc / S.A[r][k];
+  // Back-substitution, column-oriented: lane j keeps the right-hand side of its column's pivot row; once x_k is known
+  // every earlier column's lane takes its multiple of x_k off in parallel.
+  const int myrow = lane < nc ? S.piv[lane] : -1;
+  double y = myrow >= 0 ? S.A[myrow][nc] : 0.0;
+  for (int k = nc - 1; k >= 0; --k) {
+    const int r = __builtin_amdgcn_readlane(myrow, k);
+    double xk = 0.0;
+    if (r >= 0) {
+      xk = lane_bcast(y, k) / S.A[r][k];
+      if (lane < k && myrow >= 0) y = fma(-S.A[myrow][k], xk, y);
     }
+    if (lane == k) S.x[k] = xk;
   }
   __syncthreads();
 }
