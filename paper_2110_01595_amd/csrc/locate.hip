@@ -217,8 +217,8 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
     bool dependent = row >= nr;
     double akk = 0.0, tail = 0.0, nrm = 0.0;
     if (!dependent) {
-#pragma unroll 4
-      for (int i = row + 1; i < nr; ++i) tail = fma(S.A[i][k], S.A[i][k], tail);
+      const double below = (lane > row && lane < nr) ? S.A[lane][k] : 0.0;  // lane = row: the column's part below the pivot
+      tail = wave_sum_all(below * below);
       akk = S.A[row][k];
       nrm = sqrt(fma(akk, akk, tail));
       dependent = !(nrm > SOLON_RANK_TOL * S.cn[k]);
