@@ -27,6 +27,19 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), n
 
 
+def test_every_launch_shape_knob_is_documented_in_the_header():
+    """solon_tune stores unknown keys silently, so a knob the sources read but the header does not name could not be found."""
+    import glob
+
+    header = open(os.path.join(ROOT, "include", "solon.h")).read()
+    used = set()
+    for path in glob.glob(os.path.join(ROOT, "paper_2110_01595_amd", "csrc", "*.hip")):
+        used |= set(re.findall(r'solon_tuning\("([a-z_0-9]+)"', open(path).read()))
+    assert used, "no knobs found: the pattern is stale"
+    missing = sorted(k for k in used if '"%s"' % k not in header)
+    assert not missing, missing
+
+
 @pytest.mark.parametrize("r_g", list(range(1, 65)))
 def test_default_points_match_oracle(r_g):
     assert np.array_equal(solon.solon_default_points(r_g), so.default_points(r_g))
