@@ -49,6 +49,7 @@ OK, E_INVAL, E_BOUND, E_POINTS, E_DECODE, E_NUMERIC = 0, -1, -2, -3, -4, -5
 
 TAU = 1e-4          # residual test threshold, relative to the group's median |rho|
 RANK_RCOND = 1e-10  # relative singular-value cut-off of the locator system's least-squares solve
+SEARCH_LIMIT = 1 << 16  # candidate sets phi tries beyond the locator's leading roots before it gives up
 
 
 class OracleError(Exception):
@@ -205,6 +206,33 @@ def _locate_group_bruteforce(wg, rho_g, s, m, tau):
     return None
 
 
+def _locate_group_bruteforce_stacked(wg, rho_g, s, m, tau):
+    """The same enumeration as _locate_group_bruteforce with all subsets of one size fitted in one stacked QR call
+    (rows of the left-out points are zeroed instead of deleted, which leaves the least-squares solution unchanged).
+    Only quicker; the loop above is the definition, and a test holds the two equal."""
+    n = len(wg)
+    nonfinite = [i for i in range(n) if not np.isfinite(rho_g[i])]
+    sc = _scale(rho_g)
+    if sc == 0.0:
+        return nonfinite if len(nonfinite) <= s else None
+    y = np.where(np.isfinite(rho_g), rho_g / sc, 0.0)
+    A = _cheb.chebvander(wg, m - 1)
+    for e in range(len(nonfinite), s + 1):
+        subsets = [S for S in combinations(range(n), e) if all(i in S for i in nonfinite)]
+        if not subsets:
+            continue
+        keep = np.ones((len(subsets), n))
+        if e:
+            keep[np.arange(len(subsets))[:, None], np.array(subsets)] = 0.0
+        Qm, Rm = np.linalg.qr(A[None, :, :] * keep[:, :, None])
+        coef = np.linalg.solve(Rm, (Qm.transpose(0, 2, 1) @ (y[None, :] * keep)[:, :, None]))[:, :, 0]
+        res = np.abs(coef @ A.T - y[None, :])
+        ok = np.all((res <= tau) | (keep == 0.0), axis=1)
+        if ok.any():
+            return sorted(subsets[int(np.argmax(ok))])
+    return None
+
+
 def _locator_system(wg, y, m, s):
     """[W_{m+s-1}, -W_{s-1} .* (y 1^T)] a = y .* T_s(w): the system of Sec. 3.4 written in the
     Chebyshev basis (a change of basis of the unknown polynomials; the locator's leading
@@ -215,6 +243,46 @@ def _locator_system(wg, y, m, s):
     b = y * VD[:, s]
     eq = 1.0 / np.maximum(1.0, np.abs(y))
     return A * eq[:, None], b * eq
+
+
+def _accept(wf, y, S, m, tau):
+    """Is S an explanation of the data?  Fit P_j without S; every other point must lie within tau of it.
+    An accepted S is then reduced to a smallest one in the sense of App. C: a point goes back in whenever the
+    rest stays consistent with it (so an honest point that was left out needlessly is never reported, however
+    far the fit had to be extrapolated to reach it).  Returns (V, coefficients) or None."""
+    S = set(S)
+    fl, _, coef = _fit_and_test(wf, y, S, m, tau)
+    if not set(fl) <= S:
+        return None
+    reduced = True
+    while reduced:
+        reduced = False
+        for j in sorted(S):
+            fl2, _, coef2 = _fit_and_test(wf, y, S - {j}, m, tau)
+            if set(fl2) <= S - {j}:
+                S, coef, reduced = S - {j}, coef2, True
+                break
+    return sorted(S), coef
+
+
+def _candidate_sets(order, s_eff):
+    """The sets phi tries as "corrupted", in order.  `order` lists the points by increasing |D(w_i)|.
+    First the leading roots of the locator: {}, {o_0}, {o_0, o_1}, ... up to s_eff points - over the reals the first
+    of them that explains the data is the answer (Lemma 1).  In floating point a weakly corrupted point's |D| can
+    come out larger than an honest neighbour's, so the search then widens to every subset of at most s_eff points,
+    ordered by the position c of its last point in `order`, then by size, then colexicographically: all subsets of
+    the c leading points are tried before any that needs point c + 1.  Carried to the end this is the subset
+    enumeration of the sparse-recovery appendix (App. C); it stops after SEARCH_LIMIT sets."""
+    for e in range(s_eff + 1):
+        yield list(order[:e])
+    tried = 0
+    for c in range(1, len(order) + 1):
+        for e in range(1, min(s_eff, c) + 1):
+            for T in sorted(combinations(range(c - 1), e - 1), key=lambda t: t[::-1]):
+                if tried >= SEARCH_LIMIT:
+                    return
+                tried += 1
+                yield [order[t] for t in T] + [order[c - 1]]
 
 
 def _locate_group_bw(wg, rho_g, s, m, tau, want_quotient=False):
@@ -236,21 +304,18 @@ def _locate_group_bw(wg, rho_g, s, m, tau, want_quotient=False):
         # every corrupted point is a root of every solution's locator; when fewer than s nodes are corrupt the
         # locator has further, arbitrary roots, so order the points by |D(w_i)| (corrupted ones come first)
         absD = np.abs(_cheb.chebval(wf, D))
-        order = np.argsort(absD, kind="stable")[:s_eff].tolist()
+        order = np.argsort(absD, kind="stable").tolist()
     else:
         order = []
-    # P_j: the degree-(m-1) polynomial through all points except the fewest leading locator roots that leave
-    # the rest consistent (equals N / D over the reals; leaving out no more points than necessary keeps honest
-    # points from being judged by an extrapolated fit)
-    flagged = None
-    for e in range(len(order) + 1):
-        cand = set(order[:e])
-        fl, _, coef = _fit_and_test(wf, y, cand, m, tau)
-        if all(i in cand for i in fl):
-            flagged = fl
+    # P_j: the degree-(m-1) polynomial through all points but the corrupted ones (equals N / D over the reals)
+    found = None
+    for S in _candidate_sets(order, s_eff):
+        found = _accept(wf, y, S, m, tau)
+        if found is not None:
             break
-    if flagged is None:
+    if found is None:
         return None
+    flagged, coef = found
     V = sorted(nonfinite + [int(fin[i]) for i in flagged])
     if want_quotient:
         return V, _cheb.cheb2poly(coef) * sc if m > 1 else coef * sc
@@ -285,6 +350,8 @@ def locate(plan, rho, method="bw", tau=TAU):
             Vg = _locate_group_bw(wg, rho[idx], plan.s, plan.m, tau)
         elif method == "bruteforce":
             Vg = _locate_group_bruteforce(wg, rho[idx], plan.s, plan.m, tau)
+        elif method == "bruteforce_stacked":
+            Vg = _locate_group_bruteforce_stacked(wg, rho[idx], plan.s, plan.m, tau)
         elif method == "literal":
             Vg, _ = _locate_group_literal(wg, rho[idx], plan.s, plan.m, tau)
             if len(Vg) > plan.s:
