@@ -2,9 +2,12 @@
 //   1. rho_j = f R_j, accumulated in fp64 with a fixed reduction tree (project_kernel + reduce_kernel);
 //   2. per group, one wavefront builds and solves the error-locator system
 //        [W_{m+s-1}, -W_{s-1} .* (rho 1^T)] a = rho .* w^s
-//      (written in the Chebyshev basis, rows equilibrated), orders the points by |D(w_i)| (corrupted points
-//      are roots of the locator D), fits the degree-(m-1) polynomial P_j through all points except the fewest
-//      leading roots that leave the rest consistent, and flags V = {i : |P_j(w_i) - rho_i| > tau * median|rho|};
+//      (written in the Chebyshev basis, rows equilibrated) and orders the points by |D(w_i)| (corrupted points
+//      are roots of the locator D).  V is the smallest set of points without which the others lie within
+//      tau * median|rho| of one polynomial P_j of degree m-1 (Lemma 1; the sparse-recovery appendix): the
+//      leading roots of D are tried first, then - because in floating point a weakly corrupted point's |D| can
+//      come out larger than an honest neighbour's - every subset of at most s points in the order of the position
+//      of its last point among the roots, one candidate set per lane;
 //   3. the same wavefront prepares psi (Lemma 2): m well-spread honest nodes of the group and the
 //      inverse of their m x m Vandermonde (Lagrange basis coefficients), left on the device for decode.
 #include <math.h>
@@ -17,6 +20,11 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define SOLON_TAU 1e-4          // residual threshold relative to the group's median |rho|
 #define SOLON_RANK_TOL 1e-12    // a column whose remaining norm falls below this fraction is dependent
 #define SOLON_INV_NORM_MAX 1e6  // largest accepted infinity norm of the inverse m x m Vandermonde
+#define SOLON_SEARCH_LIMIT 65536      // candidate sets tried beyond the locator's leading roots before a group is given up
+#define SOLON_SPEC_SEARCH_LIMIT 1024  // the same for the guess of the one-pass entry (a wrong guess only costs time)
+#define SOLON_LANE_TEST_MAX 8         // largest locator degree whose candidate sets are tested one per lane
+#define SOLON_Y_CLAMP 1e8             // projections are clamped to this many medians in the per-lane test (see lane_test)
+#define SOLON_CHOL_MIN 1e-13          // smallest accepted pivot of the per-lane Cholesky factorisation
 
 // ------------------------------------------------------------------------------------------------
 // Projection.  grid = (row bunches, column tiles); a bunch is RB consecutive rows of R (the last bunch may hold
@@ -190,8 +198,11 @@ struct solve_smem {
   double wv[64];      // their evaluation points
   double val[64];     // scratch values compared across lanes
   double lag[SOLON_MAX_M][SOLON_MAX_M + 1];
+  double Q[64][SOLON_MAX_M + 1];  // orthonormal polynomials of degree < m over the group's points (row = point)
   double med[2];
   int piv[64];
+  int by_rank[64];    // by_rank[k] = point with the k-th smallest |D(w_i)|
+  uint32_t cnt[65];   // cnt[c] = number of candidate sets of the widened search whose last point has position < c
 };
 
 // Value of `v` in lane `src` (src must be wave-uniform): two scalar broadcasts, no LDS.
@@ -326,6 +337,260 @@ __device__ double wave_polyfit(double x, double y, bool use, int m) {
   return fit;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Candidate sets.  "Is S the corrupted set?" means: does the least-squares polynomial of degree m-1 through the points
+// outside S pass within tau of all of them.  With Q an orthonormal basis of the polynomials over ALL points of the
+// group, r = y - Q Q^T y the residual of the fit through all points and M = I - Q Q^T, leaving S out of the fit is the
+// same as giving every point of S a free parameter delta: M_SS delta = r_S, and the residuals of the other points
+// are r_k - sum_{j in S} M_kj delta_j.  That is a |S| x |S| Cholesky solve plus |S| multiply-adds per point, small
+// enough for ONE LANE, so 64 candidate sets are judged at a time.  (The projections enter clamped to +-1e8 medians:
+// a larger value can only belong to a corrupted point - the median is an honest magnitude - and inside S a point's
+// value does not matter, while unclamped its 1e-16 relative rounding would swamp tau in r.)
+
+// Binomial coefficients C(a, i), saturating at 2^30 (item numbers stay below SOLON_SEARCH_LIMIT).
+struct binom_table {
+  uint32_t c[65][34];
+};
+constexpr binom_table make_binom_table() {
+  binom_table t{};
+  for (int a = 0; a <= 64; ++a) {
+    for (int i = 0; i < 34; ++i) {
+      uint64_t v = i == 0 ? 1 : (a == 0 ? 0 : (uint64_t)t.c[a - 1][i - 1] + t.c[a - 1][i]);
+      t.c[a][i] = v > (1u << 30) ? (1u << 30) : (uint32_t)v;
+    }
+  }
+  return t;
+}
+static __device__ const binom_table g_binom = make_binom_table();
+
+__device__ __forceinline__ unsigned long long lane_bcast_mask(unsigned long long v, int src) {
+  const unsigned lo = (unsigned)__shfl((int)(unsigned)v, src, 64);
+  const unsigned hi = (unsigned)__shfl((int)(unsigned)(v >> 32), src, 64);
+  return ((unsigned long long)hi << 32) | lo;
+}
+
+// Orthonormal basis Q (by the three-term recurrence over the points, lane = point), residual r = y - Q Q^T y into
+// S.val, and M = I - Q Q^T into S.A (lane = row).  `n` points, lanes 0 .. n-1.
+__device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m, int lane) {
+  const bool pt = lane < n;
+  const double wgt = pt ? 1.0 : 0.0;
+  const double yc = fmin(fmax(y, -SOLON_Y_CLAMP), SOLON_Y_CLAMP);
+  double p_prev = 0.0, p_cur = 1.0 / sqrt((double)n), fit = 0.0;
+  double q[SOLON_MAX_M];
+#pragma unroll
+  for (int k = 0; k < SOLON_MAX_M; ++k) q[k] = 0.0;
+#pragma unroll
+  for (int k = 0; k < SOLON_MAX_M; ++k) {
+    if (k < m) {  // wave-uniform
+      q[k] = wgt * p_cur;
+      fit = fma(wave_sum(wgt * yc * p_cur), p_cur, fit);
+      if (k + 1 < m) {
+        const double xp = x * p_cur;
+        const double alpha = wave_sum(wgt * xp * p_cur);
+        const double beta = wave_sum(wgt * xp * p_prev);
+        const double t = xp - alpha * p_cur - beta * p_prev;
+        const double nrm = sqrt(wave_sum(wgt * t * t));
+        p_prev = p_cur;
+        p_cur = nrm > 1e-150 ? t / nrm : 0.0;  // fewer distinct points than coefficients cannot happen (n >= m + s)
+      }
+    }
+  }
+  __syncthreads();  // S.A, S.val are free again
+#pragma unroll
+  for (int k = 0; k < SOLON_MAX_M; ++k) S.Q[lane][k] = q[k];
+  S.val[lane] = pt ? yc - fit : 0.0;
+  __syncthreads();
+  for (int j = 0; j < n; ++j) {
+    double acc = (j == lane) ? 1.0 : 0.0;
+#pragma unroll
+    for (int k = 0; k < SOLON_MAX_M; ++k) acc = fma(-q[k], S.Q[j][k], acc);  // q[k] = 0 beyond m
+    S.A[lane][j] = acc;
+  }
+  __syncthreads();
+}
+
+// One lane's verdict on one candidate set `mask` (bits = points) of at most E points.
+template <int E>
+__device__ bool lane_test(const solve_smem& S, unsigned long long mask, int n) {
+  int el[E];
+  bool have[E];
+  double b[E], inv[E], L[E * (E + 1) / 2];
+  unsigned long long mm = mask;
+#pragma unroll
+  for (int a = 0; a < E; ++a) {
+    have[a] = mm != 0;
+    el[a] = have[a] ? __ffsll((long long)mm) - 1 : 0;
+    mm &= mm - 1;
+    b[a] = have[a] ? S.val[el[a]] : 0.0;
+  }
+  // M_SS, padded with the identity where the set has fewer than E points
+#pragma unroll
+  for (int a = 0; a < E; ++a) {
+#pragma unroll
+    for (int c = 0; c <= a; ++c) {
+      const double g = S.A[el[a]][el[c]];
+      L[a * (a + 1) / 2 + c] = have[a] ? g : (a == c ? 1.0 : 0.0);
+    }
+  }
+  bool ok = true;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    double d = L[j * (j + 1) / 2 + j];
+#pragma unroll
+    for (int k = 0; k < j; ++k) d = fma(-L[j * (j + 1) / 2 + k], L[j * (j + 1) / 2 + k], d);
+    const bool good = d > SOLON_CHOL_MIN;  // false for NaN too
+    ok = ok && good;
+    inv[j] = 1.0 / sqrt(good ? d : 1.0);
+#pragma unroll
+    for (int i = j + 1; i < E; ++i) {
+      double t = L[i * (i + 1) / 2 + j];
+#pragma unroll
+      for (int k = 0; k < j; ++k) t = fma(-L[i * (i + 1) / 2 + k], L[j * (j + 1) / 2 + k], t);
+      L[i * (i + 1) / 2 + j] = t * inv[j];
+    }
+  }
+  double dl[E];
+#pragma unroll
+  for (int a = 0; a < E; ++a) {  // L z = r_S
+    double t = b[a];
+#pragma unroll
+    for (int c = 0; c < a; ++c) t = fma(-L[a * (a + 1) / 2 + c], dl[c], t);
+    dl[a] = t * inv[a];
+  }
+#pragma unroll
+  for (int a = E - 1; a >= 0; --a) {  // L^T delta = z
+    double t = dl[a];
+#pragma unroll
+    for (int c = a + 1; c < E; ++c) t = fma(-L[c * (c + 1) / 2 + a], dl[c], t);
+    dl[a] = t * inv[a];
+  }
+  for (int k = 0; k < n; ++k) {
+    double res = S.val[k];
+#pragma unroll
+    for (int a = 0; a < E; ++a) res = fma(-S.A[el[a]][k], dl[a], res);  // delta is zero in the padding
+    const bool inside = (mask >> k) & 1ull;
+    ok = ok && (inside || fabs(res) <= SOLON_TAU);
+  }
+  return ok;
+}
+
+// The same verdict by the whole wavefront (any set size): fit through the points outside `mask`, lane = point.
+__device__ bool wave_test(double x, double y, int n, int m, unsigned long long mask, int lane) {
+  const bool keep = lane < n && !((mask >> lane) & 1ull);
+  const double fitted = wave_polyfit(x, y, keep, m);
+  return __ballot(keep && !(fabs(fitted - y) <= SOLON_TAU)) == 0;
+}
+
+struct test_ctx {
+  double x, y;  // this lane's point (compacted position = lane)
+  int n, m, se, lane;
+};
+
+// Verdicts on the candidate sets of the lanes with `active` set: bit l = lane l's set explains the group.  Locator
+// degrees above SOLON_LANE_TEST_MAX take the sets one after the other through the whole wavefront and stop at the
+// first that passes (the callers only use the lowest set bit).
+__device__ unsigned long long test_batch(const solve_smem& S, const test_ctx& c, unsigned long long mask, bool active) {
+  if (c.se <= SOLON_LANE_TEST_MAX) {
+    bool ok = false;
+    switch (c.se) {
+      case 0: case 1: ok = lane_test<1>(S, mask, c.n); break;
+      case 2: ok = lane_test<2>(S, mask, c.n); break;
+      case 3: ok = lane_test<3>(S, mask, c.n); break;
+      case 4: ok = lane_test<4>(S, mask, c.n); break;
+      case 5: ok = lane_test<5>(S, mask, c.n); break;
+      case 6: ok = lane_test<6>(S, mask, c.n); break;
+      case 7: ok = lane_test<7>(S, mask, c.n); break;
+      default: ok = lane_test<8>(S, mask, c.n); break;
+    }
+    return __ballot(active && ok);
+  }
+  unsigned long long todo = __ballot(active);
+  while (todo) {
+    const int l = __ffsll((long long)todo) - 1;
+    todo &= todo - 1;
+    if (wave_test(c.x, c.y, c.n, c.m, lane_bcast_mask(mask, l), c.lane)) return 1ull << l;
+  }
+  return 0;
+}
+
+// Candidate set number t of the widened search: sets are ordered by the position c of their last point in the
+// |D| order, then by size e = 1 .. se, then colexicographically in the other e-1 points (positions below c - 1
+// in the |D| order), so every subset of the c leading points comes before any that needs a later point.
+__device__ unsigned long long widened_set(const solve_smem& S, uint32_t t, int n, int se) {
+  int c = 1;
+  while (c < n && t >= S.cnt[c]) ++c;
+  uint32_t idx = t - S.cnt[c - 1];
+  int e = 1;
+  for (; e < se; ++e) {
+    const uint32_t ne = g_binom.c[c - 1][e - 1];
+    if (idx < ne) break;
+    idx -= ne;
+  }
+  unsigned long long mk = 1ull << S.by_rank[c - 1];
+  int a = c - 2;
+  for (int i = e - 1; i >= 1; --i) {  // combinatorial number system: the largest a with C(a, i) <= idx, then the rest
+    while (g_binom.c[a][i] > idx) --a;
+    mk |= 1ull << S.by_rank[a];
+    idx -= g_binom.c[a][i];
+    --a;
+  }
+  return mk;
+}
+
+// The located set of one group as a mask over its (finite) points, or found = false.  `drank` is this point's
+// position in the order of increasing |D(w_i)|.
+__device__ unsigned long long search_located_set(solve_smem& S, const test_ctx& c, int drank, uint32_t limit, bool* found_out) {
+  const int lane = c.lane, n = c.n, se = c.se;
+  const bool pt = lane < n;
+  if (pt) S.by_rank[drank] = lane;
+  __syncthreads();
+  if (se <= SOLON_LANE_TEST_MAX) lane_test_setup(S, c.x, c.y, n, c.m, lane);
+  // 1. the leading roots of the locator: lane e leaves out the e first points of the |D| order
+  unsigned long long mask = 0;
+  for (int k = 0; k < se; ++k)
+    if (k < lane) mask |= 1ull << S.by_rank[k];
+  unsigned long long pass = test_batch(S, c, mask, lane <= se);
+  bool found = pass != 0;
+  unsigned long long located = found ? lane_bcast_mask(mask, __ffsll((long long)pass) - 1) : 0;
+  // 2. every subset of at most se points
+  if (!found && se > 0) {
+    if (lane >= 1 && lane <= n) {
+      uint32_t cnt = 0;
+      for (int e = 1; e <= se; ++e) cnt = min(cnt + g_binom.c[lane - 1][e - 1], 1u << 30);
+      S.cnt[lane] = cnt;
+    }
+    if (lane == 0) S.cnt[0] = 0;
+    __syncthreads();
+    if (lane == 0)
+      for (int k = 1; k <= n; ++k) S.cnt[k] = min(S.cnt[k] + S.cnt[k - 1], 1u << 30);
+    __syncthreads();
+    const uint32_t total = min(S.cnt[n], limit);
+    for (uint32_t base = 0; base < total && !found; base += 64) {
+      const uint32_t t = base + lane;
+      const bool active = t < total;
+      mask = active ? widened_set(S, t, n, se) : 0;
+      pass = test_batch(S, c, mask, active);
+      if (pass) {
+        found = true;
+        located = lane_bcast_mask(mask, __ffsll((long long)pass) - 1);
+      }
+    }
+  }
+  // 3. smallest set: put back every point the others stay consistent with (lowest point first, one at a time)
+  while (found && located) {
+    const int e = __popcll(located);
+    mask = located;
+    for (int k = 0; k < lane && k < e; ++k) mask &= mask - 1;  // drop the `lane` lowest points ...
+    const unsigned long long mine = mask & (~mask + 1);          // ... the next one is this lane's
+    mask = located & ~mine;
+    pass = test_batch(S, c, mask, lane < e);
+    if (!pass) break;
+    located = lane_bcast_mask(mask, __ffsll((long long)pass) - 1);
+  }
+  *found_out = found;
+  return located;
+}
+
 // mode: SOLVE_TABLES = psi's tables for the located set already in vmask; SOLVE_LOCATE = phi, then psi's tables;
 // SOLVE_SPECULATE = phi on a projection of a sample of the columns, as a guess of the located set for the fused
 // locate + decode pass: never fails (a group it cannot explain is taken as clean) and leaves vmask and status alone.
@@ -425,19 +690,12 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
           }
           drank = wave_rank(dv, pt, nfin, lane);
         }
-        // P_j: least-squares polynomial of degree m-1 through all points except the fewest leading locator roots
-        // that leave the rest consistent.  When fewer than s nodes are corrupt the locator has further, arbitrary
-        // roots; leaving out no more points than necessary keeps honest points from being judged by an
-        // extrapolated fit.
-        unsigned long long flag_mask = 0;  // indexed by compacted position
+        // V: the smallest set of points without which the rest is consistent (leading roots first, then wider)
+        test_ctx tc;
+        tc.x = wl; tc.y = yl; tc.n = nfin; tc.m = m; tc.se = se; tc.lane = lane;
+        if (se == 0 && pt) drank = lane;
         bool consistent = false;
-        for (int ex = 0; ex <= se && !consistent; ++ex) {
-          const bool cand = pt && drank < ex;
-          const double fitted = wave_polyfit(wl, yl, pt && !cand, m);
-          const bool flag = pt && !(fabs(fitted - yl) <= SOLON_TAU);
-          flag_mask = __ballot(flag);
-          consistent = (flag_mask & ~__ballot(cand)) == 0;
-        }
+        const unsigned long long flag_mask = search_located_set(S, tc, drank, a.mode == SOLVE_SPECULATE ? SOLON_SPEC_SEARCH_LIMIT : SOLON_SEARCH_LIMIT, &consistent);
         if (!consistent) st = SOLON_E_DECODE;
         if (finite && ((flag_mask >> pos) & 1ull)) located = true;
       }

@@ -117,6 +117,7 @@ def check_config(name, cfg, sd, u_tol):
     say("  oracle projection done", round(time.time() - t_start, 1), "s")
     assert np.all(np.abs(rho - rho_ref) <= 1e-12 * mag.max())
     assert so.locate(oplan, rho_ref, "bw") == V
+    assert so.locate(oplan, rho_ref, "bruteforce_stacked") == V     # groups of at most 20 nodes: the whole enumeration is affordable
 
     # decode: sampled windows against the oracle's decode of the same R, and against the plain sum
     for p0, p1 in windows(d_c):
@@ -126,8 +127,11 @@ def check_config(name, cfg, sd, u_tol):
         uh = u[c0:c1].cpu().numpy()
         assert so.rel_l2(uh, u_ref) <= u_tol, (name, p0)
         assert so.rel_l2(uh, so.plain_sum(G[:, c0:c1].float().cpu().numpy())) <= u_tol, (name, p0)
+        rms_w = float(np.sqrt(np.mean(u_ref * u_ref)))
+        assert float((np.abs(uh - u_ref) / (np.abs(u_ref) + rms_w + 1e-300)).max()) <= 8.0 * u_tol, (name, p0)
 
-    # every coordinate: u against the fp64 column sum of G computed by torch on the device
+    # every coordinate: u against the fp64 column sum of G computed by torch on the device, in the norm and one by one
+    # (each within 8 u_tol of its own magnitude + the rms of the aggregate: a single wrong coordinate is off by about one rms)
     num = 0.0
     den = 0.0
     blk = 1 << 22
@@ -137,7 +141,12 @@ def check_config(name, cfg, sd, u_tol):
         num += float((diff * diff).sum())
         den += float((ref * ref).sum())
     rel = (num / den) ** 0.5
-    say("  rel_l2(u, G 1_P) over all d = %.3e" % rel, round(time.time() - t_start, 1), "s")
-    assert rel <= u_tol
+    rms = (den / d) ** 0.5
+    worst = 0.0
+    for c0 in range(0, d, blk):
+        ref = G[:, c0:c0 + blk].sum(dim=0, dtype=torch.float64)
+        worst = max(worst, float(((u[c0:c0 + blk].double() - ref).abs() / (ref.abs() + rms)).max()))
+    say("  rel_l2(u, G 1_P) over all d = %.3e, worst coordinate %.3e of (|u_c| + rms)" % (rel, worst), round(time.time() - t_start, 1), "s")
+    assert rel <= u_tol and worst <= 8.0 * u_tol
     del G, Z, R, u, f
     torch.cuda.empty_cache()

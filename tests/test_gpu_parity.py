@@ -1,6 +1,11 @@
 """GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
-on the same seeded inputs.  Bars: located set bit-exact; rho to 1e-12 relative; encode rel-L2 <= 1e-6;
-decoded aggregate rel-L2 <= 1e-4 (against the oracle's decode of the same R and against the plain sum)."""
+on the same seeded inputs.  Bars: located set bit-exact - against brute force (the subset enumeration of the
+sparse-recovery appendix) wherever its at most 2e5 subsets per group are affordable, against the oracle's phi and
+the planted set always; rho to 1e-12 relative; encode rel-L2 <= 1e-6 and every element within 4e-6 of the largest;
+decoded aggregate rel-L2 <= 1e-4 (against the oracle's decode of the same R and against the plain sum) and every
+coordinate within 8e-4 of (its own magnitude + the rms), for every m <= 10; m = 12 and 16 run at 5e-3."""
+from math import comb
+
 import numpy as np
 import pytest
 import torch
@@ -22,7 +27,7 @@ def host(t):
 
 
 def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, seed=0, dist="normal", sigma=0.01,
-             check_bruteforce=False, u_tol=1e-4, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False,
+             check_bruteforce=None, u_tol=1e-4, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False,
              fused=False, attack_from_column=0):
     """One encode -> attack -> locate -> decode round, compared step by step with the oracle."""
     say("case", dict(P=P, s=s, m=m, d=d, dtype=dtype, attack=attack, byz=byz, seed=seed, pad=pad))
@@ -72,8 +77,10 @@ def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, see
     V_ref = so.locate(oplan, rho_ref, "bw")
     assert V == V_ref, (V, V_ref)
     assert V == sorted(byz), (V, byz)
+    if check_bruteforce is None:    # brute force is the reference wherever it is affordable
+        check_bruteforce = max(sum(comb(len(n), e) for e in range(s + 1)) for n in oplan.nodes) <= 200_000
     if check_bruteforce:
-        assert so.locate(oplan, rho_ref, "bruteforce") == V
+        assert so.locate(oplan, rho_ref, "bruteforce_stacked") == V
 
     if not fused:
         solon.solon_decode(plan, R, u[:d], byz=V if decode_from_host else None)
@@ -84,7 +91,19 @@ def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, see
     u_ref = so.decode(oplan, Rh, V_ref, d)
     assert so.rel_l2(uh, u_ref) <= u_tol
     assert so.rel_l2(uh, so.plain_sum(Gh)) <= u_tol
+    assert_every_coordinate_close(uh, u_ref, u_tol)
     return plan
+
+
+def assert_every_coordinate_close(u, u_ref, u_tol):
+    """No single coordinate may be off: each lies within 8 u_tol of (its own magnitude + the rms of the aggregate).
+    Rounding errors of the recombination grow with the values they combine and spread like a Gaussian with the
+    rel-L2 error as its width (six widths at 1e8 coordinates), so this bound follows from the rel-L2 bar; one wrong
+    coordinate of ordinary size is off by about one rms, three decades above it."""
+    rms = float(np.sqrt(np.mean(np.square(u_ref, dtype=np.float64))))
+    err = np.abs(u.astype(np.float64) - u_ref)
+    worst = float((err / (np.abs(u_ref) + rms + 1e-300)).max()) if err.size else 0.0
+    assert worst <= 8.0 * u_tol, worst
 
 
 # ------------------------------------------------------------------ small cases: several tiles + ragged tail
@@ -98,7 +117,7 @@ SMALL = [
 
 @pytest.mark.parametrize("P,s,m,d", SMALL)
 def test_round_fp32(P, s, m, d):
-    run_case(P, s, m, d, attack="flip10", seed=P + m, check_bruteforce=(P <= 15))
+    run_case(P, s, m, d, attack="flip10", seed=P + m)
 
 
 def test_largest_compiled_compression_ratio():
@@ -272,8 +291,8 @@ def test_locate_decode_in_one_pass(grid):
         run_case(45, 2, 2, 50_002, attack="noise100", seed=58, fused=True)        # groups of 6 and 7 nodes, m = 2
         run_case(20, 2, 5, 25_003, seed=54, fused=True)                           # m = 5: falls back to the two passes
         run_case(15, 1, 2, 40_002, pad=1, seed=55, fused=True)                    # unaligned rows: falls back
-        run_case(448, 5, 4, 4_000, attack="mix", seed=59, fused=True, check_bruteforce=False)   # LDS slots for 448 nodes exceed 64 KB: falls back
-        run_case(300, 5, 4, 6_000, attack="mix", seed=60, fused=True, check_bruteforce=False)   # 300 nodes still fit
+        run_case(448, 5, 4, 4_000, attack="mix", seed=59, fused=True)   # LDS slots for 448 nodes exceed 64 KB: falls back
+        run_case(300, 5, 4, 6_000, attack="mix", seed=60, fused=True)   # 300 nodes still fit
     finally:
         solon.solon_tune("fuse", -1)
         solon.solon_tune("fuse_grid", 0)
@@ -483,8 +502,7 @@ def test_randomised_rounds_through_the_persistent_kernels():
             lo, hi = (3_000, 60_000) if grid else (200_000, 900_000)
             d = int(rng.integers(lo, hi))
             run_case(P, s, m, d, dtype=str(rng.choice(["f32", "bf16"])), attack=str(rng.choice(attacks)),
-                     n_byz=int(rng.integers(0, s + 1)), seed=7000 + case, fused=bool(rng.integers(0, 2)),
-                     u_tol=5e-3 if m >= 8 else 1e-4)
+                     n_byz=int(rng.integers(0, s + 1)), seed=7000 + case, fused=bool(rng.integers(0, 2)))
     finally:
         for knob in ("encode_phase", "decode_phase", "fuse"):
             solon.solon_tune(knob, -1)
