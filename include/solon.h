@@ -173,6 +173,24 @@ int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr, const flo
 int solon_decode_majority(solon_plan* plan, const float* R, int64_t ldr, float* u, int32_t* byz_idx, int32_t* n_byz,
                           void* hip_stream);
 
+/*
+ * solon_locate for callers that cannot allocate device memory or take part in a plan's workspace: code recorded under
+ * HIP graph capture in a process that must not call hipMalloc, tight serving loops, harnesses that forbid allocation.
+ * Same kernels, same located set and status as solon_locate, but everything they need beyond the caller's buffers (the
+ * group tables, the per-tile partial projections, psi's tables) lives in a device array that is part of the library
+ * image: about 1.03 MiB held on every GPU the library runs on, until the process ends.  The plan is only read on the
+ * host (its own workspace may be missing), no HIP allocation, free, memset or host copy is made, and the call never waits.
+ *   R, f      device, as for solon_locate
+ *   located   device int32[P] (written: 1 = node in V, 0 = not; idle nodes 0)
+ *   status    device int32[q] (written: SOLON_OK / SOLON_E_DECODE / SOLON_E_NUMERIC per group)
+ *   rho       device double[P] or NULL (written: the projections)
+ * Limits: P <= 128 (SOLON_E_INVAL beyond).  All calls on one GPU share the one array and it keeps the last call's
+ * contents: calls that overlap on one GPU (different streams or threads) race and must be ordered by the caller.  Every
+ * part a call reads is written by that call first; located[] is cleared by it.
+ */
+int solon_locate_static(const solon_plan* plan, const float* R, int64_t ldr, const float* f, int32_t* located, int32_t* status,
+                        double* rho, void* hip_stream);
+
 /* Waits for hip_stream and returns the status the last solon_locate / solon_decode on this plan left on the
  * device: SOLON_OK, SOLON_E_DECODE or SOLON_E_NUMERIC. */
 int solon_decode_status(solon_plan* plan, void* hip_stream);

@@ -5,5 +5,5 @@ from .solon import (  # noqa: F401
     SOLON_F32, SOLON_BF16,
     SOLON_Q_GROUPS, SOLON_Q_REDUNDANCY, SOLON_Q_MESSAGE_LEN, SOLON_Q_MAX_GROUP, SOLON_Q_WORKSPACE, SOLON_Q_HAS_DEVICE,
     lib, solon_decode, solon_decode_majority, solon_decode_status, solon_default_points, solon_encode, solon_locate,
-    solon_locate_decode, solon_tune,
+    solon_locate_decode, solon_locate_static, solon_tune,
 )

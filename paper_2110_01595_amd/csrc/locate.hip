@@ -134,8 +134,8 @@ static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipSt
 #undef SOLON_LAUNCH
 }
 
-int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles_out,
-                           hipStream_t st) {
+int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
+                              int64_t ncols, int tile_base, int* ntiles_out, hipStream_t st) {
   const int P = plan->P;
   // rows per bunch: the fewest bunches of at most 16 rows, of equal size where P allows.  With the XCD-aware block
   // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing (measured at P = 100:
@@ -149,14 +149,14 @@ int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const 
   const int64_t strips = std::max<int64_t>(1, (work + 255) / 256);
   // strips per tile: 4 to 32 (measured best: 32 once there are well over 6000 blocks, 4 for small inputs), and
   // enough to keep the partial-sum table within its allocation
-  const int64_t room = SOLON_PROJ_MAX_TILES - tile_base;
+  const int64_t room = max_tiles - tile_base;
   int64_t seg = solon_tuning("project_seg", 0);
   if (seg <= 0) seg = std::min<int64_t>(32, std::max<int64_t>(4, strips * nbunch / 6000));
   seg = std::max<int64_t>(seg, (strips + room - 1) / room);
   const int64_t ntiles = (strips + seg - 1) / seg;
   *ntiles_out = (int)ntiles;
   const bool xcd_map = solon_tuning("project_xcd_map", 1) != 0 && nbunch > 1;
-  double* partials = plan->dev.partials + (int64_t)tile_base * P;
+  double* partials = D.partials + (int64_t)tile_base * P;
   switch (rb) {
 #define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, ncols, P, (int)seg, partials); break;
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
@@ -172,12 +172,18 @@ int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const 
   return SOLON_OK;
 }
 
-int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st) {
-  plan->proj_tiles = ntiles;
-  hipLaunchKernelGGL(reduce_kernel, dim3(plan->P), dim3(256), 0, st, plan->dev.partials, ntiles, plan->P, plan->dev.rho);
+int solon_project_reduce_on(const solon_plan* plan, const solon_dev& D, int ntiles, hipStream_t st) {
+  hipLaunchKernelGGL(reduce_kernel, dim3(plan->P), dim3(256), 0, st, D.partials, ntiles, plan->P, D.rho);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
+
+int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles_out,
+                           hipStream_t st) {
+  return solon_project_partials_on(plan, plan->dev, SOLON_PROJ_MAX_TILES, R, ldr, f, ncols, tile_base, ntiles_out, st);
+}
+
+int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st) { return solon_project_reduce_on(plan, plan->dev, ntiles, st); }
 
 int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const float* f, hipStream_t st) {
   int ntiles = 0;
@@ -774,23 +780,25 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   if (lane == 0 && a.mode != SOLVE_SPECULATE) a.status[g] = st;
 }
 
-int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st) {
+int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, hipStream_t st) {
   solve_args a;
   a.s = plan->s; a.m = plan->m; a.mode = mode;
-  a.grp_off = plan->dev.grp_off; a.grp_nodes = plan->dev.grp_nodes; a.w = plan->dev.w; a.rho = plan->dev.rho;
-  a.vmask = plan->dev.vmask; a.status = plan->dev.status; a.redo = plan->dev.redo;
+  a.grp_off = D.grp_off; a.grp_nodes = D.grp_nodes; a.w = D.w; a.rho = D.rho;
+  a.vmask = D.vmask; a.status = D.status; a.redo = D.redo;
   a.guess_rows = nullptr;
-  a.order = plan->dev.spec_order;
-  a.dec_rows = plan->dev.dec_rows; a.dec_coef = plan->dev.dec_coef;
+  a.order = D.spec_order;
+  a.dec_rows = D.dec_rows; a.dec_coef = D.dec_coef;
   if (mode == SOLVE_SPECULATE) {
-    a.dec_rows = plan->dev.spec_rows; a.dec_coef = plan->dev.spec_coef;
+    a.dec_rows = D.spec_rows; a.dec_coef = D.spec_coef;
   } else if (mode == SOLVE_LOCATE_CHECK) {
-    a.mode = SOLVE_LOCATE; a.guess_rows = plan->dev.spec_rows;
+    a.mode = SOLVE_LOCATE; a.guess_rows = D.spec_rows;
   }
   hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
+
+int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st) { return solon_launch_solve_on(plan, plan->dev, mode, st); }
 
 int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host /*P or null*/, double* rho_host /*P or null*/) {
   // staging layout: [double rho[P]] [int32 vmask[P]] [int32 status[q]]

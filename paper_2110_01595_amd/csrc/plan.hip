@@ -194,7 +194,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->P = P; p->B = B; p->s = s; p->m = m; p->r = r; p->q = q; p->dtype = grad_dtype;
   p->d = d; p->d_c = (d + m - 1) / m;
   p->group_of_node = gon; p->group_of_batch = gob;
-  p->ws = nullptr; p->ws_bytes = 0; p->pinned = nullptr; p->pinned_bytes = 0; p->proj_tiles = 0;
+  p->ws = nullptr; p->ws_bytes = 0; p->pinned = nullptr; p->pinned_bytes = 0;
   p->grp_off.assign(q + 1, 0);
   p->bat_off.assign(q + 1, 0);
   for (int j = 0; j < P; ++j) if (gon[j] >= 0) p->grp_off[gon[j] + 1]++;
@@ -318,6 +318,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
     delete p;
     return solon_hip_fail(le, "workspace initialisation");
   }
+  (void)solon_static_prepare();  // set-up of solon_locate_static on this device; a failure is reported by that call itself
   *out = p;
   return SOLON_OK;
 }

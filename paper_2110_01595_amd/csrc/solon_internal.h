@@ -49,7 +49,6 @@ struct solon_plan {
   solon_dev dev;
   void* pinned;        // hipHostMalloc staging for small host <-> device transfers
   size_t pinned_bytes;
-  int proj_tiles;      // tiles used by the last projection launch
 };
 
 void solon_set_error(const char* fmt, ...);
@@ -83,9 +82,16 @@ int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st);
 // writes the guess tables only); phi that also raises the redo flag when its rows differ from the guess
 enum { SOLVE_TABLES = 0, SOLVE_LOCATE = 1, SOLVE_SPECULATE = 2, SOLVE_LOCATE_CHECK = 3 };
 int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st);
+// the same three steps on a table of device buffers other than the plan's own workspace (`max_tiles` = rows of D.partials)
+int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
+                              int64_t ncols, int tile_base, int* ntiles, hipStream_t st);
+int solon_project_reduce_on(const solon_plan* plan, const solon_dev& D, int ntiles, hipStream_t st);
+int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, hipStream_t st);
 // waits for the stream, copies status (and optionally the located mask and rho) to the host, returns the worst group status
 int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host, double* rho_host);
 // run_flag: device int32 or null; when it points at 0 the kernels return at once (u already holds the result)
 int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st);
 // chunks p_start .. d_c - 1 only (p_start a multiple of four), with the general kernel
 int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t ldr, float* u, int64_t p_start, hipStream_t st);
+// asks for the device address of the library's static scratch array on the current device (kept per device)
+int solon_static_prepare(void);

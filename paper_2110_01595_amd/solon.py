@@ -19,7 +19,7 @@ SOLON_Q_GROUPS, SOLON_Q_REDUNDANCY, SOLON_Q_MESSAGE_LEN, SOLON_Q_MAX_GROUP, SOLO
 EXPORTS = [
     "solon_plan_create", "solon_plan_destroy", "solon_plan_query", "solon_plan_groups", "solon_plan_points",
     "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_locate_decode", "solon_decode_majority",
-    "solon_decode_status",
+    "solon_decode_status", "solon_locate_static",
     "solon_tune",
     "solon_last_error",
 ]
@@ -67,6 +67,8 @@ def lib():
     L.solon_locate_decode.restype = i32
     L.solon_decode_majority.argtypes = [vp, vp, i64, vp, vp, vp, vp]
     L.solon_decode_majority.restype = i32
+    L.solon_locate_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp]
+    L.solon_locate_static.restype = i32
     L.solon_decode_status.argtypes = [vp, vp]
     L.solon_decode_status.restype = i32
     L.solon_tune.argtypes = [ctypes.c_char_p, i32]
@@ -206,6 +208,14 @@ def solon_decode_majority(plan, R, u, want_host=True, stream=None):
     n = ctypes.c_int32(0)
     _check(lib().solon_decode_majority(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(u), _np_ptr(idx), ctypes.byref(n), _stream(stream)))
     return idx[: n.value].tolist()
+
+
+def solon_locate_static(plan, R, f, located, status, rho=None, stream=None):
+    """The allocation-free locate: located int32[P], status int32[q] and (optional) rho float64[P] are CUDA tensors (written)."""
+    assert R.is_cuda and f.is_cuda and located.is_cuda and status.is_cuda and R.stride(1) == 1 and f.is_contiguous()
+    assert located.is_contiguous() and status.is_contiguous() and (rho is None or (rho.is_cuda and rho.is_contiguous()))
+    _check(lib().solon_locate_static(plan._h, _dev_ptr(R), R.stride(0), _dev_ptr(f), _dev_ptr(located), _dev_ptr(status),
+                                     _dev_ptr(rho) if rho is not None else None, _stream(stream)))
 
 
 def solon_decode_status(plan, stream=None):
