@@ -1,14 +1,18 @@
 """Benchmark of the Solon hot path on one MI355X: encode -> locate -> decode per step.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--also C4] [--no-cpu-baseline]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C5] [--also C4,C3,C2,X1] [--no-cpu-baseline]
 
 A step is one pass of the whole path over one batch of synthetic gradients that are already resident in
 HBM: solon_encode (G -> Z), then phi and psi (R, f -> V, u) on one stream - by default through solon_locate_decode,
 which does both in one pass over R; --two-pass times solon_locate and solon_decode as separate calls instead (the
 default run also reports those, from a few extra steps outside the timed region).
 R is the encoder's output with the configuration's Byzantine rows overwritten; that harness step runs once,
-before the timed region, into its own buffer, so each timed step moves exactly the method's bytes.
-Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).
+before the timed region, into its own buffer, so each timed step moves exactly the method's bytes.  Every step
+projects with a fresh f (drawn before the timed region).
+Prints ONE JSON line (metric, value, roofline of the dominant kernel, CPU-oracle baseline).  Throughput is given twice:
+against the ALGORITHMIC bytes of the three passes (encode, locate, decode: the numerator the metric is defined on) and
+against the bytes the timed calls really MOVE (the one-pass path reads R once: fewer bytes in the same time).
+`redo_path_ms` is the one-pass call when its guess of the honest rows is wrong and the recombination runs twice.
 """
 import argparse
 import json
@@ -34,6 +38,18 @@ def algorithmic_bytes(cfg, plan):
     return dict(encode=enc, locate=loc, decode=dec, total=enc + loc + dec)
 
 
+def moved_bytes(cfg, plan, one_pass):
+    """Bytes the timed calls move.  Two passes: the algorithmic bytes.  One pass: R and f once, u once, plus the sample
+    projection behind the guess (2^17 columns of every row)."""
+    ab = algorithmic_bytes(cfg, plan)
+    if not one_pass:
+        return dict(encode=ab["encode"], locate_decode=ab["locate"] + ab["decode"], total=ab["total"])
+    P, d, d_c = cfg["P"], cfg["d"], plan.d_c
+    sample = min(d_c, 1 << 17)
+    ld = P * d_c * 4 + d_c * 4 + d * 4 + (P + 1) * sample * 4
+    return dict(encode=ab["encode"], locate_decode=ld, total=ab["encode"] + ld)
+
+
 def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False, two_pass=False):
     import numpy as np
     import torch
@@ -54,7 +70,8 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     ld = (d_c + 63) // 64 * 64                             # rows of Z and R start on 256-byte boundaries
     Z = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
     u = torch.empty(d, dtype=torch.float32, device=dev)
-    f = workloads.make_projection(d_c, dev, sd["f"])
+    fs = [workloads.make_projection(d_c, dev, sd["f"] + 100 * k) for k in range(min(steps, 32))]   # a fresh f every step
+    f = fs[0]
     byz = workloads.pick_byzantine(P, s, sd["byz"])
     solon.solon_encode(plan, G, Z)
     R = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
@@ -62,7 +79,7 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
     torch.cuda.synchronize()
 
-    def step(events=None, one_pass=not two_pass):
+    def step(events=None, one_pass=not two_pass, f=f):
         if events is not None:
             events[0].record()
         solon.solon_encode(plan, G, Z)
@@ -87,11 +104,16 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
-        step(ev[k])
+        step(ev[k], f=fs[k % len(fs)])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     status = solon.solon_decode_status(plan)
-    V, _ = solon.solon_locate(plan, R, f)               # after the timed region: the located set, for the record
+    one_pass = (not two_pass) and plan.query(solon.SOLON_Q_LAST_ONE_PASS) == 1
+    redone = plan.query(solon.SOLON_Q_LAST_REDO) if one_pass else 0
+    located_ok = status == 0
+    for fk in (fs[0], fs[-1]):                           # after the timed region: the located set, for the record
+        V, _ = solon.solon_locate(plan, R, fk)
+        located_ok = located_ok and V == byz
     ms_step = (t1 - t0) * 1e3 / steps
     phase = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev])   # ms
     enc_ms, loc_ms, dec_ms = phase.mean(axis=0).tolist()
@@ -103,20 +125,53 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
             step(e, one_pass=False)
         torch.cuda.synchronize()
         two = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in ev2]).mean(axis=0).tolist()
+    mb = moved_bytes(cfg, plan, one_pass)
     res = dict(
         workload=name, P=P, s=s, m=m, d=d, d_c=d_c, q=plan.q, r=plan.r, grad_dtype=cfg["dtype"], attack=cfg["attack"],
-        located_ok=(status == 0 and V == byz), ms_per_step=ms_step,
+        located_ok=located_ok, ms_per_step=ms_step,
         coords_per_s=P * d / (ms_step * 1e-3),
         effective_GBps=ab["total"] / (ms_step * 1e-3) / 1e9,
+        pct_of_peak=100.0 * ab["total"] / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         algorithmic_bytes=ab,
+        path="encode + " + ("locate + decode (two passes)" if two_pass else "locate_decode (one pass over R)" if one_pass
+                            else "locate_decode (fell back to two passes: m not in {1, 2, 4} or input too small)"),
+        bytes_moved=mb, GBps_moved=mb["total"] / (ms_step * 1e-3) / 1e9,
+        pct_of_peak_moved=100.0 * mb["total"] / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        fresh_f_per_step=len(fs), recombination_repeated_in_last_step=bool(redone),
     )
     if two_pass:
         res["phase_ms"] = dict(encode=enc_ms, locate=loc_ms, decode=dec_ms)
         res["phase_GBps"] = dict(encode=ab["encode"] / enc_ms / 1e6, locate=ab["locate"] / loc_ms / 1e6, decode=ab["decode"] / dec_ms / 1e6)
+        res["phase_GBps_moved"] = res["phase_GBps"]
     else:
         res["phase_ms"] = dict(encode=enc_ms, locate_decode=loc_ms)
         res["phase_GBps"] = dict(encode=ab["encode"] / enc_ms / 1e6, locate_decode=(ab["locate"] + ab["decode"]) / loc_ms / 1e6)
+        res["phase_GBps_moved"] = dict(encode=mb["encode"] / enc_ms / 1e6, locate_decode=mb["locate_decode"] / loc_ms / 1e6)
         res["two_pass_phase_ms"] = dict(encode=two[0], locate=two[1], decode=two[2])
+        two_ms = sum(two)
+        res["two_pass"] = dict(ms_per_step=two_ms, GBps=ab["total"] / two_ms / 1e6, pct_of_peak=100.0 * ab["total"] / two_ms / 1e6 / PEAK_HBM_GBS)
+    if one_pass:
+        # worst case of the one-pass call: the guess of the honest rows is wrong (here: made blind, with the first node of
+        # group 0 - which a clean group's choice always takes - among the corrupted) and the recombination runs twice
+        first = int(plan.groups().tolist().index(0))
+        byz_w = sorted(set([first] + [j for j in byz if j != first][: max(0, s - 1)]))
+        R.copy_(Z)
+        workloads.apply_attack(R, byz_w, cfg["attack"], sd["attack"])
+        solon.solon_tune("fuse_blind_guess", 1)
+        try:
+            solon.solon_locate_decode(plan, R, f, u, want_host=False)
+            n_redo = max(3, steps // 4)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for k in range(n_redo):
+                solon.solon_locate_decode(plan, R, fs[k % len(fs)], u, want_host=False)
+            e1.record()
+            torch.cuda.synchronize()
+            res["redo_path_ms"] = dict(locate_decode=e0.elapsed_time(e1) / n_redo, step=enc_ms + e0.elapsed_time(e1) / n_redo,
+                                       recombination_repeated=bool(plan.query(solon.SOLON_Q_LAST_REDO)),
+                                       located_ok=(solon.solon_locate(plan, R, f)[0] == byz_w))
+        finally:
+            solon.solon_tune("fuse_blind_guess", 0)
     if check_sum:   # Def. 1 of the paper over every coordinate: u against the fp64 column sum of G (torch, on the device)
         num = den = 0.0
         for c0 in range(0, d, 1 << 22):
@@ -127,15 +182,22 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
         res["rel_l2_u_vs_plain_sum"] = (num / den) ** 0.5
     cpu = None
     if want_cpu_baseline:
+        if one_pass:                                          # the redo measurement changed R: back to the configuration's attack
+            R.copy_(Z)
+            workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
         cpu = cpu_baseline(cfg, plan, G, R, f, byz)
-    del G, Z, R, u, f
+    del G, Z, R, u, f, fs
     torch.cuda.empty_cache()
     return res, cpu
 
 
 def cpu_baseline(cfg, plan, G, R, f, byz):
     """The fp64 oracle as it stands, timed on the host on a bounded sample of the same workload: consecutive
-    windows of W chunks of every row (all P nodes, all steps of the path) until about 10 s of oracle time."""
+    windows of W chunks of every row (all P nodes, all steps of the path).  Two legs of about 10 s each: one thread,
+    and all host cores (one window per worker thread at a time - the oracle's numpy calls release the interpreter
+    lock - with numpy's own thread pool held at one thread in both legs, so that `cores` is what actually ran)."""
+    import concurrent.futures as cf
+
     import numpy as np
     from threadpoolctl import threadpool_limits
 
@@ -144,28 +206,51 @@ def cpu_baseline(cfg, plan, G, R, f, byz):
     P, s, m = cfg["P"], cfg["s"], cfg["m"]
     W = int(min(plan.d_c, max(1024, 4.0e8 // (P * m))))      # about 4e8 per-batch coordinates per window
     oplan = so.make_plan(P, s, m)
-    spent, coords, nwin, ok = 0.0, 0, 0, True
-    while spent < 10.0 and nwin < 12 and nwin * W < plan.d_c:
-        p0 = nwin * W
+    nwin_max = -(-plan.d_c // W)
+
+    def load(k, W=W):
+        p0 = k * W
         p1 = min(plan.d_c, p0 + W)
         c0, c1 = p0 * m, min(cfg["d"], p1 * m)
-        Gh = G[:, c0:c1].float().cpu().numpy()
-        Rh = R[:, p0:p1].cpu().numpy()
-        fh = f[p0:p1].cpu().numpy()
-        with threadpool_limits(limits=1):                     # so that "cores" below is what actually ran
+        return G[:, c0:c1].float().cpu().numpy(), R[:, p0:p1].cpu().numpy(), f[p0:p1].cpu().numpy(), c1 - c0
+
+    def work(win):
+        Gh, Rh, fh, n = win
+        Zo = so.encode(oplan, Gh)
+        rho = so.project(Rh, fh)
+        V = so.locate(oplan, rho)
+        uo = so.decode(oplan, Rh, V, n)
+        return (V == byz) and so.rel_l2(uo, so.plain_sum(Gh)) < 1e-4 and Zo.shape == Rh.shape, P * n
+
+    # leg 1: one thread
+    spent, coords, nwin, ok = 0.0, 0, 0, True
+    with threadpool_limits(limits=1):
+        while spent < 10.0 and nwin < min(12, nwin_max):
+            win = load(nwin)
             t0 = time.perf_counter()
-            Zo = so.encode(oplan, Gh)
-            rho = so.project(Rh, fh)
-            V = so.locate(oplan, rho)
-            uo = so.decode(oplan, Rh, V, c1 - c0)
+            good, n = work(win)
             spent += time.perf_counter() - t0
-        ok = ok and (V == byz) and so.rel_l2(uo, so.plain_sum(Gh)) < 1e-4 and Zo.shape == Rh.shape
-        coords += P * (c1 - c0)
-        nwin += 1
-        del Gh, Rh, fh, Zo, uo
-    return dict(value=coords / spent, unit="coords/s", cores=1, kind="oracle",
-                sample="%d consecutive windows of %d chunks (of %d) of every row (P=%d rows), each one encode+project+locate+decode; "
-                       "%.1f s of oracle time in total; located set %s" % (nwin, W, plan.d_c, P, spent, "matches" if ok else "MISMATCH"))
+            ok, coords, nwin = ok and good, coords + n, nwin + 1
+            del win
+    one = dict(value=coords / spent, unit="coords/s", cores=1, kind="oracle",
+               sample="%d consecutive windows of %d chunks (of %d) of every row (P=%d rows), each one encode+project+locate+decode; "
+                      "%.1f s of oracle time in total; located set %s" % (nwin, W, plan.d_c, P, spent, "matches" if ok else "MISMATCH"))
+    # leg 2: all host cores (at most 16, the share of a one-GPU machine), sized from leg 1 to about 10 s
+    # (windows of a quarter of the size, to bound host memory: every worker holds one window and its fp64 copies)
+    cores = max(1, min(16, os.cpu_count() or 1))
+    W2 = max(1024, W // 4)
+    per_win = spent / max(1, nwin) * W2 / W
+    rounds = max(1, min(int(10.0 / max(1.5 * per_win, 1e-3)), 8))
+    todo = cores * rounds
+    wins = [load(k, W2) for k in range(min(cores, -(-plan.d_c // W2)))]   # loaded before the clock starts; later rounds reuse them
+    with threadpool_limits(limits=1), cf.ThreadPoolExecutor(max_workers=cores) as pool:
+        t0 = time.perf_counter()
+        out = list(pool.map(work, [wins[k % len(wins)] for k in range(todo)]))
+        wall = time.perf_counter() - t0
+    one["all_cores"] = dict(value=sum(n for _, n in out) / wall, unit="coords/s", cores=min(cores, todo), kind="oracle",
+                            sample="%d windows of %d chunks on %d worker threads, %.1f s wall; results %s"
+                                   % (todo, W2, min(cores, todo), wall, "match" if all(g for g, _ in out) else "MISMATCH"))
+    return one
 
 
 # Shapes of the paper's own cost study (time-breakdown figures of Sec. 4 and of the appendix): P = 100 nodes,
@@ -244,7 +329,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="C5")
-    ap.add_argument("--also", default="C4", help="comma-separated further workloads reported inside the same line ('' = none)")
+    ap.add_argument("--also", default="C4,C3,C2,X1", help="comma-separated further workloads reported inside the same line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-pass", action="store_true", help="time solon_locate + solon_decode instead of solon_locate_decode")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
@@ -301,13 +386,20 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.config, **{k: main_res[k] for k in ("P", "s", "m", "d", "d_c", "q", "r", "grad_dtype", "attack")}},
-        "effective_GBps": main_res["effective_GBps"], "pct_of_peak": 100.0 * main_res["effective_GBps"] / PEAK_HBM_GBS,
-        "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"],
-        "two_pass_phase_ms": main_res.get("two_pass_phase_ms"), "located_ok": main_res["located_ok"],
+        "path": main_res["path"],
+        "effective_GBps": main_res["effective_GBps"], "pct_of_peak": main_res["pct_of_peak"],
+        "bytes_algorithmic": main_res["algorithmic_bytes"], "bytes_moved": main_res["bytes_moved"],
+        "GBps_moved": main_res["GBps_moved"], "pct_of_peak_moved": main_res["pct_of_peak_moved"],
+        "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"], "phase_GBps_moved": main_res["phase_GBps_moved"],
+        "two_pass_phase_ms": main_res.get("two_pass_phase_ms"), "two_pass": main_res.get("two_pass"),
+        "redo_path_ms": main_res.get("redo_path_ms"), "fresh_f_per_step": main_res["fresh_f_per_step"],
+        "located_ok": main_res["located_ok"],
         "roofline": {"kernel": "encode_phase_kernel (solon_encode; the persistent phase-separated encoder serves this size)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
-                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic},
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic,
+                     "traffic_source": "profiles/traffic.json: FETCH_SIZE + WRITE_SIZE of a separate rocprofv3 --pmc run of this command, not measured in this run"},
         "cpu_baseline": cpu,
-        "also": [{k: r[k] for k in ("workload", "ms_per_step", "coords_per_s", "effective_GBps", "phase_ms", "phase_GBps", "located_ok")
+        "also": [{k: r.get(k) for k in ("workload", "path", "ms_per_step", "coords_per_s", "effective_GBps", "pct_of_peak", "GBps_moved",
+                                        "pct_of_peak_moved", "phase_ms", "phase_GBps", "phase_GBps_moved", "redo_path_ms", "located_ok")
                   + (() if args.two_pass else ("two_pass_phase_ms",))} for r in others],
     }
     print(json.dumps(line))

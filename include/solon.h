@@ -65,7 +65,12 @@ enum solon_query {
   SOLON_Q_MESSAGE_LEN = 2, /* d_c = ceil(d / m)                                   */
   SOLON_Q_MAX_GROUP = 3,   /* largest group size                                  */
   SOLON_Q_WORKSPACE = 4,   /* bytes of device workspace owned by the plan         */
-  SOLON_Q_HAS_DEVICE = 5   /* 1 if the device workspace was allocated, else 0     */
+  SOLON_Q_HAS_DEVICE = 5,  /* 1 if the device workspace was allocated, else 0     */
+  SOLON_Q_LAST_REDO = 6,   /* 1 if the last solon_locate_decode on this plan had to repeat the recombination because one of
+                              the guessed rows was located (waits for the device; a diagnostic, not part of the path)     */
+  SOLON_Q_LIMIT_GROUP = 7, /* largest group the library handles (SOLON_MAX_GROUP); plan may be NULL                        */
+  SOLON_Q_LIMIT_M = 8,     /* largest compression ratio m with compiled kernels; plan may be NULL                          */
+  SOLON_Q_LAST_ONE_PASS = 9 /* 1 if the last solon_locate_decode on this plan ran the one-pass kernel, 0 if it took the two passes */
 };
 
 #define SOLON_MAX_GROUP 64 /* nodes per group handled by the single-wavefront locator */
@@ -143,11 +148,13 @@ int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* b
 
 /*
  * solon_locate followed by solon_decode, in one pass over R (same paper passages; same V, same status, u to the same
- * bar).  The rows for psi are guessed first - by the locator itself, run on the projection of a leading sample of the
- * columns - and the single pass over R produces the exact projections of all P rows together with the recombination
- * of the guessed rows.  The locator then runs on the exact projections as in solon_locate; only if one of the guessed
- * rows turns out to be in V (possible only when a node corrupts nothing but columns outside the sample) the
- * recombination is repeated with the right rows, decided on the device.  Reads R about once instead of
+ * bar).  The rows for psi are guessed first - by the locator itself, run on the projection of a sample of the columns
+ * (128 tiles of 1024 columns at positions hashed from the bits of f, which no sender of R knows) - and the single pass
+ * over R produces the exact projections of all P rows together with the recombination of the guessed rows.  The locator
+ * then runs on the exact projections as in solon_locate; only if one of the guessed rows turns out to be in V (a node
+ * that corrupts a fraction x of its columns escapes the sample with probability (1 - x)^128) the recombination is
+ * repeated with the right rows, decided on the device.  When a group's status is not SOLON_OK, u is unspecified.
+ * Reads R about once instead of
  * 1 + q m / P times.  Falls back to the two separate passes for m other than 1, 2, 4, unaligned buffers, plans with
  * idle nodes and small inputs.
  *   R, f            device, as for solon_locate
@@ -200,7 +207,9 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
  * "decode_phase_grid" (cap on the persistent grid, 0 = none), "phase_spin_limit", "project_rows", "project_seg",
  * "encode_blocks", "encode_nt", "encode_force_generic", "decode_blocks", "decode_ch", "decode_force_generic",
  * "fuse" (-1 = solon_locate_decode chooses by size, 0 = always two passes, 1 = one pass wherever legal), "fuse_grid",
- * "fuse_sample" (columns of the sample projection behind the guess), "fuse_spin_limit", "project_xcd_map",
+ * "fuse_sample" (columns of the sample projection behind the guess), "fuse_sample_leading" (1 = the sample is the leading
+ * columns instead of tiles at positions hashed from f: lets a test keep a corruption out of the sample), "fuse_blind_guess"
+ * (1 = the guess ignores the sample and takes every node as honest: times the repeated recombination), "fuse_spin_limit", "project_xcd_map",
  * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced),
  * "majority_rows" (-1 = solon_decode_majority chooses by size, 0 = flat kernels, 1 = the persistent kernel wherever legal),
  * "majority_rows_grid".

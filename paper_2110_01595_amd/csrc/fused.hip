@@ -6,9 +6,10 @@
 // rows, and the error-locator solve on the exact projections decides - as in solon_locate - which nodes are
 // corrupt.  If none of the guessed rows is among them the recombination already is the result; otherwise (a device-side
 // flag, no host round trip) the ordinary recombination kernels run after all.  The guess comes from the locator
-// itself, run on the projection of a small leading sample of the columns: a node whose corruption shows in the
-// sample is avoided, so the second pass is needed only against an adversary that corrupts nothing but columns
-// outside the sample.  The located set and the status never depend on the guess.
+// itself, run on the projection of a small sample of the columns: a node whose corruption shows in the sample is
+// avoided.  The sample is 128 tiles of 1024 columns at positions hashed from the bits of this call's f, which the
+// senders of R cannot know: a node that corrupts a fraction x of its columns stays out of the sample only with
+// probability (1 - x)^128, whatever columns it chooses.  The located set and the status never depend on the guess.
 //
 // The pass is a persistent grid; each round a thread takes one float4 column unit through all rows: the fp64 partial
 // projection of every row (reduced over each wavefront by lane permutations, over the block through LDS, one partial
@@ -219,6 +220,7 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
   int64_t per_pass = 0;
   const int grid = fused_grid(plan, R, ldr, f, u, nunits, &per_pass);
   int rc;
+  plan->last_one_pass = grid != 0;
   if (grid == 0) {  // the two passes of solon_locate + solon_decode
     rc = solon_launch_project(plan, R, ldr, f, st);
     if (rc != SOLON_OK) return rc;
@@ -230,7 +232,9 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
     // 1. the guess: phi on the projection of the leading sample columns
     int ntiles = 0;
     const int64_t sample = std::min<int64_t>(plan->d_c, std::max(4, solon_tuning("fuse_sample", FUSE_SAMPLE)));
-    rc = solon_project_partials(plan, R, ldr, f, sample, 0, &ntiles, st);
+    // tiles of the sample sit at positions hashed from this call's f wherever the rows are long enough to choose from
+    const bool hashed = plan->d_c >= 4 * sample && plan->d_c >= 8192 && solon_tuning("fuse_sample_leading", 0) == 0;
+    rc = solon_project_partials(plan, R, ldr, f, sample, 0, &ntiles, st, hashed ? plan->d_c : 0);
     if (rc != SOLON_OK) return rc;
     rc = solon_project_reduce(plan, ntiles, st);
     if (rc != SOLON_OK) return rc;

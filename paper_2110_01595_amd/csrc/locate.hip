@@ -32,9 +32,15 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // row of its bunch and walks its strips with 16-byte loads, so f is loaded once per RB rows of R.  All RB loads of
 // a strip are issued back to back with no branch between them: a bunch with fewer rows re-reads its last row
 // (in bounds, served by the cache) and drops those sums.
+//
+// sample_total > 0 turns the launch into a SAMPLE of the columns (the guess of the one-pass locate + decode): tile t then
+// covers the hashed position h(key, t) among the sample_total whole tiles of a row, with the key taken from the bits of
+// this call's f - which a sender of R cannot know, so no node can keep its corruption out of the sample on purpose.
+// A position drawn twice only weights its columns twice: the projections of honest rows stay values of one polynomial.
 template <int RB, bool VEC, bool XCD_MAP>
 __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ R, int64_t ldr, const float* __restrict__ f,
-                                                       int64_t d_c, int P, int seg, int nbunch, int ntiles, double* __restrict__ partials) {
+                                                       int64_t d_c, int P, int seg, int nbunch, int ntiles, double* __restrict__ partials,
+                                                       uint32_t sample_total) {
   // Block -> (tile, bunch).  Workgroups are handed to the eight XCDs round-robin, each with its own L2: block L runs
   // on XCD L % 8 as that XCD's (L / 8)-th block.  Numbering the work so that consecutive blocks OF ONE XCD are the
   // bunches of one tile lets all bunches of a tile find its piece of f in that XCD's L2.
@@ -60,7 +66,15 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
     acc[i] = 0.0;
     rp[i] = R + (int64_t)(row0 + min(i, nrows - 1)) * ldr;
   }
-  const int64_t first = (int64_t)tile * seg * 256 + tid;
+  int64_t tpos = tile;
+  if (sample_total > 0) {
+    const uint32_t key = __float_as_uint(f[0]) ^ (__float_as_uint(f[1]) << 11 | __float_as_uint(f[1]) >> 21) ^
+                         (__float_as_uint(f[2]) << 22 | __float_as_uint(f[2]) >> 10) ^ (__float_as_uint(f[3]) * 0x9E3779B9u);
+    uint32_t h = key + 0x9E3779B9u * (uint32_t)(tile + 1);  // the 32-bit finaliser of MurmurHash3
+    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
+    tpos = (int64_t)(((uint64_t)h * (uint64_t)sample_total) >> 32);
+  }
+  const int64_t first = tpos * seg * 256 + tid;
   if (VEC) {
     const int64_t nvec = d_c / 4;
     for (int it = 0; it < seg; ++it) {
@@ -79,7 +93,7 @@ __global__ __launch_bounds__(256) void project_kernel(const float* __restrict__ 
         acc[i] = fma(f3, (double)rv[i].w, acc[i]);
       }
     }
-    if (tile == 0 && tid < (int)(d_c - nvec * 4)) {  // fewer than four trailing columns
+    if (sample_total == 0 && tile == 0 && tid < (int)(d_c - nvec * 4)) {  // fewer than four trailing columns
       const int64_t c = nvec * 4 + tid;
       const double fc = f[c];
 #pragma unroll
@@ -123,10 +137,10 @@ __global__ __launch_bounds__(256) void reduce_kernel(const double* __restrict__ 
 
 template <int RB>
 static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipStream_t st, const float* R, int64_t ldr, const float* f,
-                           int64_t d_c, int P, int seg, double* partials) {
+                           int64_t d_c, int P, int seg, double* partials, uint32_t sample_total) {
   const int64_t total = (int64_t)nbunch * ntiles;
   const dim3 grid((unsigned)(xcd_map ? (total + 7) / 8 * 8 : total));
-#define SOLON_LAUNCH(V, X) hipLaunchKernelGGL((project_kernel<RB, V, X>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, nbunch, ntiles, partials)
+#define SOLON_LAUNCH(V, X) hipLaunchKernelGGL((project_kernel<RB, V, X>), grid, dim3(256), 0, st, R, ldr, f, d_c, P, seg, nbunch, ntiles, partials, sample_total)
   if (vec && xcd_map) SOLON_LAUNCH(true, true);
   else if (vec) SOLON_LAUNCH(true, false);
   else if (xcd_map) SOLON_LAUNCH(false, true);
@@ -135,7 +149,7 @@ static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipSt
 }
 
 int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
-                              int64_t ncols, int tile_base, int* ntiles_out, hipStream_t st) {
+                              int64_t ncols, int tile_base, int* ntiles_out, hipStream_t st, int64_t sample_of) {
   const int P = plan->P;
   // rows per bunch: the fewest bunches of at most 16 rows, of equal size where P allows.  With the XCD-aware block
   // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing (measured at P = 100:
@@ -152,13 +166,17 @@ int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int ma
   const int64_t room = max_tiles - tile_base;
   int64_t seg = solon_tuning("project_seg", 0);
   if (seg <= 0) seg = std::min<int64_t>(32, std::max<int64_t>(4, strips * nbunch / 6000));
+  if (sample_of > 0) seg = 1;  // a sample: many small tiles, each at a hashed position of the row
   seg = std::max<int64_t>(seg, (strips + room - 1) / room);
   const int64_t ntiles = (strips + seg - 1) / seg;
   *ntiles_out = (int)ntiles;
+  // whole tiles in a row of sample_of columns (the caller makes sure there is at least one)
+  const uint32_t sample_total = sample_of > 0 ? (uint32_t)std::min<int64_t>((vec ? sample_of / 4 : sample_of) / (seg * 256), 0x7fffffff) : 0u;
+  const int64_t row_cols = sample_of > 0 ? sample_of : ncols;
   const bool xcd_map = solon_tuning("project_xcd_map", 1) != 0 && nbunch > 1;
   double* partials = D.partials + (int64_t)tile_base * P;
   switch (rb) {
-#define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, ncols, P, (int)seg, partials); break;
+#define SOLON_CASE(N) case N: project_launch<N>(vec, xcd_map, nbunch, (int)ntiles, st, R, ldr, f, row_cols, P, (int)seg, partials, sample_total); break;
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
     SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
     SOLON_CASE(17) SOLON_CASE(18) SOLON_CASE(19) SOLON_CASE(20) SOLON_CASE(21) SOLON_CASE(22) SOLON_CASE(23) SOLON_CASE(24)
@@ -179,8 +197,8 @@ int solon_project_reduce_on(const solon_plan* plan, const solon_dev& D, int ntil
 }
 
 int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles_out,
-                           hipStream_t st) {
-  return solon_project_partials_on(plan, plan->dev, SOLON_PROJ_MAX_TILES, R, ldr, f, ncols, tile_base, ntiles_out, st);
+                           hipStream_t st, int64_t sample_of) {
+  return solon_project_partials_on(plan, plan->dev, SOLON_PROJ_MAX_TILES, R, ldr, f, ncols, tile_base, ntiles_out, st, sample_of);
 }
 
 int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st) { return solon_project_reduce_on(plan, plan->dev, ntiles, st); }
@@ -602,6 +620,7 @@ __device__ unsigned long long search_located_set(solve_smem& S, const test_ctx& 
 // locate + decode pass: never fails (a group it cannot explain is taken as clean) and leaves vmask and status alone.
 struct solve_args {
   int s, m, mode;
+  int blind;                  // SOLVE_SPECULATE: skip phi and guess that every node is honest (times the repeated recombination)
   const int32_t* guess_rows;  // SOLVE_LOCATE: rows a speculative recombination used, or null
   int32_t* redo;              // set to 1 when some group's rows differ from guess_rows; SOLVE_SPECULATE clears it
   int32_t* order;             // SOLVE_SPECULATE: every group's nodes, the chosen rows first
@@ -627,7 +646,9 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   bool located = false;
   if (a.mode == SOLVE_SPECULATE && g == 0 && lane == 0) *a.redo = 0;
 
-  if (a.mode != SOLVE_TABLES) {
+  if (a.mode == SOLVE_SPECULATE && a.blind) {
+    // nothing located: psi's tables below are those of a clean group
+  } else if (a.mode != SOLVE_TABLES) {
     const double rho = in_group ? a.rho[node] : 0.0;
     const bool finite = in_group && isfinite(rho);
     const unsigned long long fin_mask = __ballot(finite);
@@ -783,6 +804,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
 int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, hipStream_t st) {
   solve_args a;
   a.s = plan->s; a.m = plan->m; a.mode = mode;
+  a.blind = mode == SOLVE_SPECULATE && solon_tuning("fuse_blind_guess", 0) != 0;
   a.grp_off = D.grp_off; a.grp_nodes = D.grp_nodes; a.w = D.w; a.rho = D.rho;
   a.vmask = D.vmask; a.status = D.status; a.redo = D.redo;
   a.guess_rows = nullptr;

@@ -194,7 +194,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->P = P; p->B = B; p->s = s; p->m = m; p->r = r; p->q = q; p->dtype = grad_dtype;
   p->d = d; p->d_c = (d + m - 1) / m;
   p->group_of_node = gon; p->group_of_batch = gob;
-  p->ws = nullptr; p->ws_bytes = 0; p->pinned = nullptr; p->pinned_bytes = 0;
+  p->ws = nullptr; p->ws_bytes = 0; p->pinned = nullptr; p->pinned_bytes = 0; p->last_one_pass = 0;
   p->grp_off.assign(q + 1, 0);
   p->bat_off.assign(q + 1, 0);
   for (int j = 0; j < P; ++j) if (gon[j] >= 0) p->grp_off[gon[j] + 1]++;
@@ -331,11 +331,29 @@ extern "C" void solon_plan_destroy(solon_plan* plan) {
 }
 
 extern "C" int solon_plan_query(const solon_plan* plan, int what, int64_t* value) {
+  if (value && what == SOLON_Q_LIMIT_GROUP) {
+    *value = SOLON_MAX_GROUP;
+    return SOLON_OK;
+  }
+  if (value && what == SOLON_Q_LIMIT_M) {
+    *value = SOLON_MAX_M;
+    return SOLON_OK;
+  }
   if (!plan || !value) {
     solon_set_error("solon_plan_query: null argument");
     return SOLON_E_INVAL;
   }
   switch (what) {
+    case SOLON_Q_LAST_ONE_PASS: *value = plan->last_one_pass; break;
+    case SOLON_Q_LAST_REDO: {
+      int32_t flag = 0;
+      if (plan->ws) {
+        SOLON_HIP(hipDeviceSynchronize());
+        SOLON_HIP(hipMemcpy(&flag, plan->dev.redo, sizeof(flag), hipMemcpyDeviceToHost));
+      }
+      *value = flag;
+      break;
+    }
     case SOLON_Q_GROUPS: *value = plan->q; break;
     case SOLON_Q_REDUNDANCY: *value = plan->r; break;
     case SOLON_Q_MESSAGE_LEN: *value = plan->d_c; break;

@@ -49,6 +49,7 @@ struct solon_plan {
   solon_dev dev;
   void* pinned;        // hipHostMalloc staging for small host <-> device transfers
   size_t pinned_bytes;
+  int last_one_pass;   // 1 if the last solon_locate_decode ran the one-pass kernel, 0 if it fell back to the two passes
 };
 
 void solon_set_error(const char* fmt, ...);
@@ -75,7 +76,10 @@ int solon_launch_project(solon_plan* plan, const float* R, int64_t ldr, const fl
 // the two halves of solon_launch_project: per-tile partial projections of columns [0, ncols) of R and f, written to tiles
 // tile_base, tile_base + 1, ... of the plan's table (*ntiles receives how many); and the fixed-order sum of the first
 // ntiles tiles into rho
-int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles, hipStream_t st);
+// With sample_of > 0 the launch projects a SAMPLE of about ncols columns of rows that are sample_of columns long: tiles of
+// 1024 columns at positions hashed from the bits of f (needs sample_of >= 2048; positions are whole tiles inside the row).
+int solon_project_partials(solon_plan* plan, const float* R, int64_t ldr, const float* f, int64_t ncols, int tile_base, int* ntiles, hipStream_t st,
+                           int64_t sample_of = 0);
 int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st);
 // modes of the per-group solve wavefront: psi's tables for the located set already on the device; phi, then psi's
 // tables; phi on a projection of a sample of the columns as a guess for the fused locate + decode pass (never fails,
@@ -84,7 +88,7 @@ enum { SOLVE_TABLES = 0, SOLVE_LOCATE = 1, SOLVE_SPECULATE = 2, SOLVE_LOCATE_CHE
 int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st);
 // the same three steps on a table of device buffers other than the plan's own workspace (`max_tiles` = rows of D.partials)
 int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
-                              int64_t ncols, int tile_base, int* ntiles, hipStream_t st);
+                              int64_t ncols, int tile_base, int* ntiles, hipStream_t st, int64_t sample_of = 0);
 int solon_project_reduce_on(const solon_plan* plan, const solon_dev& D, int ntiles, hipStream_t st);
 int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, hipStream_t st);
 // waits for the stream, copies status (and optionally the located mask and rho) to the host, returns the worst group status

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libsolon.so")
 SOLON_OK, SOLON_E_INVAL, SOLON_E_BOUND, SOLON_E_POINTS, SOLON_E_DECODE, SOLON_E_NUMERIC, SOLON_E_HIP = 0, -1, -2, -3, -4, -5, -6
 SOLON_F32, SOLON_BF16 = 0, 1
 SOLON_Q_GROUPS, SOLON_Q_REDUNDANCY, SOLON_Q_MESSAGE_LEN, SOLON_Q_MAX_GROUP, SOLON_Q_WORKSPACE, SOLON_Q_HAS_DEVICE = range(6)
+SOLON_Q_LAST_REDO, SOLON_Q_LIMIT_GROUP, SOLON_Q_LIMIT_M, SOLON_Q_LAST_ONE_PASS = 6, 7, 8, 9
 
 EXPORTS = [
     "solon_plan_create", "solon_plan_destroy", "solon_plan_query", "solon_plan_groups", "solon_plan_points",

@@ -271,6 +271,7 @@ def test_locate_decode_in_one_pass(grid):
     solon.solon_tune("fuse", 1)
     solon.solon_tune("fuse_grid", grid)
     solon.solon_tune("fuse_sample", 256)
+    solon.solon_tune("fuse_sample_leading", 1)            # so that attack_from_column keeps a corruption out of the sample
     try:
         run_case(63, 3, 4, 131_075, seed=41, fused=True)                          # d not a multiple of 4 m: trailing columns
         run_case(63, 3, 4, 131_072, attack="mix", seed=42, fused=True)
@@ -297,6 +298,58 @@ def test_locate_decode_in_one_pass(grid):
         solon.solon_tune("fuse", -1)
         solon.solon_tune("fuse_grid", 0)
         solon.solon_tune("fuse_sample", 1 << 17)
+        solon.solon_tune("fuse_sample_leading", 0)
+
+
+def test_the_guess_sample_cannot_be_avoided_through_a_fixed_window():
+    """Adversaries that leave the leading quarter of every row alone.  Against a sample of the LEADING columns they are
+    invisible to the guess, the guessed rows (a clean group's choice starts with its first node, which is corrupt here)
+    turn out located and the recombination runs twice - every round.  Against the sample at positions hashed from f
+    they are seen (16 tiles, each inside the corrupted part with probability 3/4), the guess avoids them and no round
+    repeats the recombination.  Either way V, the status and u are those of the two separate passes."""
+    P, s, m, d = 63, 3, 4, 2_000_000
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    G = workloads.make_gradients(cfg, DEV, 81, d=d)
+    Z = torch.zeros((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    byz = [int(oplan.nodes[g][0]) for g in (0, 2, 5)]
+    R = workloads.apply_attack(Z.clone(), byz, "mix", 82)
+    R[:, :plan.d_c // 4] = Z[:, :plan.d_c // 4]
+    ua, ub = torch.zeros(d, dtype=torch.float32, device=DEV), torch.zeros(d, dtype=torch.float32, device=DEV)
+    solon.solon_tune("fuse", 1)
+    solon.solon_tune("fuse_sample", 16384)
+    try:
+        for leading, expect_redo in ((1, 8), (0, 0)):
+            solon.solon_tune("fuse_sample_leading", leading)
+            redone = 0
+            for k in range(8):
+                f = workloads.make_projection(plan.d_c, DEV, 900 + k)      # a fresh f every round
+                Va, _ = solon.solon_locate(plan, R, f)
+                solon.solon_decode(plan, R, ua)
+                ub.zero_()
+                Vb, _ = solon.solon_locate_decode(plan, R, f, ub)
+                redone += plan.query(solon.SOLON_Q_LAST_REDO)
+                assert Va == Vb == byz and torch.equal(ua, ub)
+            say("sample leading" if leading else "sample hashed", "rounds that repeated the recombination:", redone, "of 8")
+            assert redone == expect_redo
+        # a narrow window (1 % of the columns) may or may not meet the sample: the result does not depend on it
+        R = workloads.apply_attack(Z.clone(), byz, "noise100", 83)
+        lo = plan.d_c // 2
+        R[:, :lo] = Z[:, :lo]
+        R[:, lo + plan.d_c // 100:] = Z[:, lo + plan.d_c // 100:]
+        for k in range(4):
+            f = workloads.make_projection(plan.d_c, DEV, 950 + k)
+            Va, _ = solon.solon_locate(plan, R, f)
+            solon.solon_decode(plan, R, ua)
+            ub.zero_()
+            Vb, _ = solon.solon_locate_decode(plan, R, f, ub)
+            assert Va == Vb == byz and torch.equal(ua, ub)
+    finally:
+        solon.solon_tune("fuse", -1)
+        solon.solon_tune("fuse_sample", 1 << 17)
+        solon.solon_tune("fuse_sample_leading", 0)
 
 
 def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
@@ -311,6 +364,7 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
     try:
         solon.solon_tune("fuse", 1)
         solon.solon_tune("fuse_sample", 1024)
+        solon.solon_tune("fuse_sample_leading", 1)
         for byz, from_col in (([], 0), ([3, 40, 62], 0), ([3, 40, 62], 2048), ([0, 1, 2], 5000)):
             R = workloads.apply_attack(Z.clone(), byz, "mix", 63)
             if from_col:
@@ -332,6 +386,7 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
     finally:
         solon.solon_tune("fuse", -1)
         solon.solon_tune("fuse_sample", 1 << 17)
+        solon.solon_tune("fuse_sample_leading", 0)
 
 
 def test_step_can_be_captured_in_a_hip_graph_and_replayed():
