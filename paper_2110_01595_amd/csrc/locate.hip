@@ -298,41 +298,132 @@ __device__ void wave_least_squares(solve_smem& S, int nr, int nc, int lane) {
   __syncthreads();
 }
 
+// |D(w_i)| for locator degrees up to SOLON_LANE_TEST_MAX without forming the system matrix: the same least-squares
+// problem as wave_least_squares solves (numerator columns first, then the locator's, rows equilibrated), with lane =
+// point.  The numerator's column space - polynomials of degree < m + se times the row scaling - gets an orthonormal
+// basis from the three-term recurrence over the points, one degree at a time; the se + 1 columns y T_k(w) of the
+// locator and the right-hand side are made orthogonal to each basis vector as it appears; what is left of them is a
+// least-squares problem in the se locator coefficients alone, solved by Gram-Schmidt on those columns.  Two rounds
+// of wavefront sums per degree (the se + 3 sums of a round share their latency) instead of a Householder sweep per
+// column through LDS.  Only the first `rows` rows of 16 lanes hold points.
+template <int SE>  // SE = locator degree
+__device__ double locator_abs_values(double wl, double yl, bool pt, int m, int rows) {
+  const double eq = pt ? 1.0 / fmax(1.0, fabs(yl)) : 0.0;  // row scaling; lanes without a point weigh nothing
+  double c[SE + 1], cn0[SE + 1];
+  {
+    double t0 = 1.0, t1 = wl;
+#pragma unroll
+    for (int k = 0; k <= SE; ++k) {
+      c[k] = eq * yl * t0;
+      const double t2 = 2.0 * wl * t1 - t0;
+      t0 = t1;
+      t1 = t2;
+    }
+  }
+  double p_prev = 0.0, p_cur;
+  {
+    double v[SE + 2];
+#pragma unroll
+    for (int k = 0; k <= SE; ++k) v[k] = c[k] * c[k];
+    v[SE + 1] = eq * eq;
+    wave_sums<SE + 2>(v, rows);
+#pragma unroll
+    for (int k = 0; k <= SE; ++k) cn0[k] = sqrt(v[k]);
+    p_cur = eq / sqrt(v[SE + 1]);
+  }
+  const int nn = m + SE;
+  for (int j = 0; j < nn; ++j) {
+    const double xp = wl * p_cur;
+    double v[SE + 3];
+#pragma unroll
+    for (int k = 0; k <= SE; ++k) v[k] = c[k] * p_cur;
+    v[SE + 1] = xp * p_cur;
+    v[SE + 2] = xp * p_prev;
+    wave_sums<SE + 3>(v, rows);
+#pragma unroll
+    for (int k = 0; k <= SE; ++k) c[k] = fma(-v[k], p_cur, c[k]);
+    if (j + 1 == nn) break;
+    const double q = xp - v[SE + 1] * p_cur - v[SE + 2] * p_prev;
+    const double nrm = sqrt(wave_sum_rows(q * q, rows));
+    p_prev = p_cur;
+    p_cur = nrm > 1e-150 ? q / nrm : 0.0;
+  }
+  // Gram-Schmidt on what is left of the locator columns; a column that has (numerically) nothing left is dependent on
+  // the earlier ones and gets coefficient zero, which picks one of the system's solutions (Lemma l9, case ii)
+  double r[SE][SE + 1];
+  bool dep[SE];
+#pragma unroll
+  for (int k = 0; k < SE; ++k) {
+    const double nk = sqrt(wave_sum_rows(c[k] * c[k], rows));
+    dep[k] = !(nk > SOLON_RANK_TOL * cn0[k]);
+    const double qk = dep[k] ? 0.0 : c[k] / nk;
+    r[k][k] = nk;
+    double v[SE];
+#pragma unroll
+    for (int j = 1; j <= SE; ++j) v[j - 1] = j > k ? qk * c[j] : 0.0;
+    wave_sums<SE>(v, rows);
+#pragma unroll
+    for (int j = k + 1; j <= SE; ++j) {
+      r[k][j] = v[j - 1];
+      c[j] = fma(-r[k][j], qk, c[j]);
+    }
+  }
+  // sum_k x_k c_k ~ c_SE; the locator's coefficients are d_k = -x_k (the columns enter the system with a minus sign)
+  double x[SE];
+#pragma unroll
+  for (int k = SE - 1; k >= 0; --k) {
+    double t = r[k][SE];
+#pragma unroll
+    for (int j = k + 1; j < SE; ++j) t = fma(-r[k][j], x[j], t);
+    x[k] = dep[k] ? 0.0 : t / r[k][k];
+  }
+  double dv = 0.0, t0 = 1.0, t1 = wl;
+#pragma unroll
+  for (int k = 0; k <= SE; ++k) {
+    dv = fma(k < SE ? -x[k < SE ? k : 0] : 1.0, t0, dv);
+    const double t2 = 2.0 * wl * t1 - t0;
+    t0 = t1;
+    t1 = t2;
+  }
+  return fabs(dv);
+}
+
 // Number of lanes (among `active`, all below `n`) whose value precedes this lane's in the total order (value, lane).
-__device__ int wave_rank(double v, bool active, int n, int lane) {
+// The values go through LDS (`slot`, 64 doubles): every lane reads them back one by one, all lanes the same address.
+__device__ int wave_rank(double* slot, double v, bool active, int n, int lane) {
   const unsigned long long mask = __ballot(active);
+  __syncthreads();
+  slot[lane] = v;
+  __syncthreads();
   int rank = 0;
   for (int j = 0; j < n; ++j) {
-    const double o = lane_bcast(v, j);
+    const double o = slot[j];
     if ((mask >> j) & 1ull) rank += (o < v || (o == v && j < lane)) ? 1 : 0;
   }
+  __syncthreads();
   return rank;
 }
 
-// Lane holding the largest `key` among the lanes with `valid` set, the lowest such lane on ties (-1 if there is none):
-// the reduction pattern of wave_sum_lane63 on (key, lane) pairs.  A lane outside a step's row mask, or without a
-// source lane, meets its own pair again, which changes nothing.
+// Lane holding the largest `key` (never negative) among the lanes with `valid` set, the lowest such lane on ties (-1 if
+// there is none), among the first `rows` rows of 16 lanes.  The key's bit pattern - which orders non-negative doubles
+// like integers - has its seven lowest bits replaced by 127 - lane, so one unsigned 64-bit maximum finds both.
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ void dpp_best(double& key, int& idx) {
-  const int lo = __builtin_amdgcn_update_dpp(__double2loint(key), __double2loint(key), CTRL, ROW_MASK, 0xF, false);
-  const int hi = __builtin_amdgcn_update_dpp(__double2hiint(key), __double2hiint(key), CTRL, ROW_MASK, 0xF, false);
-  const int oi = __builtin_amdgcn_update_dpp(idx, idx, CTRL, ROW_MASK, 0xF, false);
-  const double ok = __hiloint2double(hi, lo);
-  const bool take = ok > key || (ok == key && oi < idx);
-  key = take ? ok : key;
-  idx = take ? oi : idx;
+__device__ __forceinline__ void dpp_max_u64(unsigned long long& k) {
+  const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp((int)(unsigned)k, (int)(unsigned)k, CTRL, ROW_MASK, 0xF, false);
+  const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp((int)(unsigned)(k >> 32), (int)(unsigned)(k >> 32), CTRL, ROW_MASK, 0xF, false);
+  const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+  k = o > k ? o : k;
 }
-__device__ int wave_argmax(double key, bool valid, int lane) {
-  double k = valid ? key : -1.0;  // keys are products of distances: never negative
-  int i = valid ? lane : 64;
-  dpp_best<0xB1, 0xF>(k, i);   // quad_perm [1,0,3,2]
-  dpp_best<0x4E, 0xF>(k, i);   // quad_perm [2,3,0,1]
-  dpp_best<0x141, 0xF>(k, i);  // row_half_mirror
-  dpp_best<0x140, 0xF>(k, i);  // row_mirror
-  dpp_best<0x142, 0xA>(k, i);  // row_bcast:15 into rows 1 and 3
-  dpp_best<0x143, 0xC>(k, i);  // row_bcast:31 into rows 2 and 3
-  const int best = __builtin_amdgcn_readlane(i, 63);
-  return best < 64 ? best : -1;
+__device__ int wave_argmax(double key, bool valid, int lane, int rows) {
+  unsigned long long k = valid ? (((unsigned long long)__double_as_longlong(key) & ~127ull) | (unsigned long long)(127 - lane)) : 0ull;
+  dpp_max_u64<0xB1, 0xF>(k);   // quad_perm [1,0,3,2]
+  dpp_max_u64<0x4E, 0xF>(k);   // quad_perm [2,3,0,1]
+  dpp_max_u64<0x141, 0xF>(k);  // row_half_mirror
+  dpp_max_u64<0x140, 0xF>(k);  // row_mirror
+  if (rows > 1) dpp_max_u64<0x142, 0xA>(k);  // row_bcast:15 into rows 1 and 3
+  if (rows > 2) dpp_max_u64<0x143, 0xC>(k);  // row_bcast:31 into rows 2 and 3
+  const int low = __builtin_amdgcn_readlane((int)(unsigned)k, __builtin_amdgcn_readfirstlane(rows * 16 - 1));
+  return (low & 127) >= 64 ? 127 - (low & 127) : -1;
 }
 
 // Sum over the wavefront, identical bits in every lane.
@@ -395,25 +486,27 @@ __device__ __forceinline__ unsigned long long lane_bcast_mask(unsigned long long
 
 // Orthonormal basis Q (by the three-term recurrence over the points, lane = point), residual r = y - Q Q^T y into
 // S.val, and M = I - Q Q^T into S.A (lane = row).  `n` points, lanes 0 .. n-1.
+template <int MM>  // MM >= m: number of basis polynomials the registers hold
 __device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m, int lane) {
   const bool pt = lane < n;
+  const int rows = n <= 16 ? 1 : n <= 32 ? 2 : 4;
   const double wgt = pt ? 1.0 : 0.0;
   const double yc = fmin(fmax(y, -SOLON_Y_CLAMP), SOLON_Y_CLAMP);
-  double p_prev = 0.0, p_cur = 1.0 / sqrt((double)n), fit = 0.0;
-  double q[SOLON_MAX_M];
+  double p_prev = 0.0, p_cur = wgt / sqrt((double)n), fit = 0.0;
+  double q[MM];
 #pragma unroll
-  for (int k = 0; k < SOLON_MAX_M; ++k) q[k] = 0.0;
+  for (int k = 0; k < MM; ++k) q[k] = 0.0;
 #pragma unroll
-  for (int k = 0; k < SOLON_MAX_M; ++k) {
+  for (int k = 0; k < MM; ++k) {
     if (k < m) {  // wave-uniform
-      q[k] = wgt * p_cur;
-      fit = fma(wave_sum(wgt * yc * p_cur), p_cur, fit);
+      q[k] = p_cur;
+      const double xp = x * p_cur;
+      double v[3] = {yc * p_cur, xp * p_cur, xp * p_prev};
+      wave_sums<3>(v, rows);
+      fit = fma(v[0], p_cur, fit);
       if (k + 1 < m) {
-        const double xp = x * p_cur;
-        const double alpha = wave_sum(wgt * xp * p_cur);
-        const double beta = wave_sum(wgt * xp * p_prev);
-        const double t = xp - alpha * p_cur - beta * p_prev;
-        const double nrm = sqrt(wave_sum(wgt * t * t));
+        const double t = xp - v[1] * p_cur - v[2] * p_prev;
+        const double nrm = sqrt(wave_sum_rows(t * t, rows));
         p_prev = p_cur;
         p_cur = nrm > 1e-150 ? t / nrm : 0.0;  // fewer distinct points than coefficients cannot happen (n >= m + s)
       }
@@ -421,13 +514,13 @@ __device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m,
   }
   __syncthreads();  // S.A, S.val are free again
 #pragma unroll
-  for (int k = 0; k < SOLON_MAX_M; ++k) S.Q[lane][k] = q[k];
+  for (int k = 0; k < MM; ++k) S.Q[lane][k] = q[k];
   S.val[lane] = pt ? yc - fit : 0.0;
   __syncthreads();
   for (int j = 0; j < n; ++j) {
     double acc = (j == lane) ? 1.0 : 0.0;
 #pragma unroll
-    for (int k = 0; k < SOLON_MAX_M; ++k) acc = fma(-q[k], S.Q[j][k], acc);  // q[k] = 0 beyond m
+    for (int k = 0; k < MM; ++k) acc = fma(-q[k], S.Q[j][k], acc);  // q[k] = 0 beyond m
     S.A[lane][j] = acc;
   }
   __syncthreads();
@@ -568,14 +661,44 @@ __device__ unsigned long long search_located_set(solve_smem& S, const test_ctx& 
   const bool pt = lane < n;
   if (pt) S.by_rank[drank] = lane;
   __syncthreads();
-  if (se <= SOLON_LANE_TEST_MAX) lane_test_setup(S, c.x, c.y, n, c.m, lane);
-  // 1. the leading roots of the locator: lane e leaves out the e first points of the |D| order
+  if (se <= SOLON_LANE_TEST_MAX) {
+    if (c.m <= 4) lane_test_setup<4>(S, c.x, c.y, n, c.m, lane);
+    else if (c.m <= 8) lane_test_setup<8>(S, c.x, c.y, n, c.m, lane);
+    else if (c.m <= 12) lane_test_setup<12>(S, c.x, c.y, n, c.m, lane);
+    else lane_test_setup<SOLON_MAX_M>(S, c.x, c.y, n, c.m, lane);
+  }
+  // 1. the leading roots of the locator: lane e <= se leaves out the e first points of the |D| order.  The lanes after
+  // them (one candidate set per lane) already try each of those sets with one of its points but the last put back -
+  // without the last one it is the next smaller leading set - so that step 3 can usually be skipped.
+  const bool per_lane = se <= SOLON_LANE_TEST_MAX;
+  int e_of = lane <= se ? lane : -1, j_of = -1;
+  if (per_lane && lane > se) {
+    int idx = lane - (se + 1);
+    for (int e = 2; e <= se; ++e) {
+      if (idx < e - 1) {
+        e_of = e;
+        j_of = idx;
+        break;
+      }
+      idx -= e - 1;
+    }
+  }
   unsigned long long mask = 0;
   for (int k = 0; k < se; ++k)
-    if (k < lane) mask |= 1ull << S.by_rank[k];
-  unsigned long long pass = test_batch(S, c, mask, lane <= se);
-  bool found = pass != 0;
-  unsigned long long located = found ? lane_bcast_mask(mask, __ffsll((long long)pass) - 1) : 0;
+    if (k < e_of && k != j_of) mask |= 1ull << S.by_rank[k];
+  unsigned long long pass = test_batch(S, c, mask, e_of >= 0);
+  const unsigned long long lead = pass & ((2ull << se) - 1ull);
+  bool found = lead != 0;
+  bool reduce = true;  // is step 3 still to be done
+  unsigned long long located = 0;
+  if (found) {
+    const int e = __ffsll((long long)lead) - 1;
+    located = lane_bcast_mask(mask, e);
+    if (per_lane) {  // lanes se + 1 + (e - 2)(e - 1) / 2 ... hold this set's put-backs
+      const int first = se + 1 + (e - 2) * (e - 1) / 2;
+      reduce = e >= 2 && ((pass >> first) & ((1ull << (e - 1)) - 1ull)) != 0;
+    }
+  }
   // 2. every subset of at most se points
   if (!found && se > 0) {
     if (lane >= 1 && lane <= n) {
@@ -596,12 +719,13 @@ __device__ unsigned long long search_located_set(solve_smem& S, const test_ctx& 
       pass = test_batch(S, c, mask, active);
       if (pass) {
         found = true;
+        reduce = true;
         located = lane_bcast_mask(mask, __ffsll((long long)pass) - 1);
       }
     }
   }
   // 3. smallest set: put back every point the others stay consistent with (lowest point first, one at a time)
-  while (found && located) {
+  while (found && reduce && located) {
     const int e = __popcll(located);
     mask = located;
     for (int k = 0; k < lane && k < e; ++k) mask &= mask - 1;  // drop the `lane` lowest points ...
@@ -660,7 +784,7 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
     } else if (nfin > 0) {
       // scale: median |rho| over the finite entries (honest nodes are a strict majority); max if that is zero
       const double ar = fabs(rho);
-      const int rk = wave_rank(ar, finite, n, lane);
+      const int rk = wave_rank(S.x, ar, finite, n, lane);
       if (finite && rk == (nfin - 1) / 2) S.med[0] = ar;
       if (finite && rk == nfin / 2) S.med[1] = ar;
       __syncthreads();
@@ -689,33 +813,47 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
         if (se > 0) {
           const int nn = m + se;      // numerator unknowns (Chebyshev coefficients 0 .. m+se-1)
           const int nc = nn + se;     // + locator unknowns (coefficients 0 .. se-1; T_se has coefficient one)
-          if (pt) {
-            const double eq = 1.0 / fmax(1.0, fabs(yl));
-            double t0 = 1.0, t1 = wl;
-            for (int k = 0; k < nn; ++k) {  // se < nn
-              if (k < nn) S.A[lane][k] = t0 * eq;
-              if (k < se) S.A[lane][nn + k] = -yl * t0 * eq;
-              if (k == se) S.A[lane][nc] = yl * t0 * eq;
-              const double t2 = 2.0 * wl * t1 - t0;
-              t0 = t1;
-              t1 = t2;
-            }
-          }
-          __syncthreads();
-          wave_least_squares(S, nfin, nc, lane);
-          // |D(w_i)|: every corrupted point is a root of every solution's locator polynomial
           double dv = 0.0;
-          if (pt) {
-            double t0 = 1.0, t1 = wl;
-            for (int k = 0; k <= se; ++k) {
-              dv = fma(k < se ? S.x[nn + k] : 1.0, t0, dv);
-              const double t2 = 2.0 * wl * t1 - t0;
-              t0 = t1;
-              t1 = t2;
+          if (se <= SOLON_LANE_TEST_MAX) {
+            const int rows = nfin <= 16 ? 1 : nfin <= 32 ? 2 : 4;
+            switch (se) {
+              case 1: dv = locator_abs_values<1>(wl, yl, pt, m, rows); break;
+              case 2: dv = locator_abs_values<2>(wl, yl, pt, m, rows); break;
+              case 3: dv = locator_abs_values<3>(wl, yl, pt, m, rows); break;
+              case 4: dv = locator_abs_values<4>(wl, yl, pt, m, rows); break;
+              case 5: dv = locator_abs_values<5>(wl, yl, pt, m, rows); break;
+              case 6: dv = locator_abs_values<6>(wl, yl, pt, m, rows); break;
+              case 7: dv = locator_abs_values<7>(wl, yl, pt, m, rows); break;
+              default: dv = locator_abs_values<8>(wl, yl, pt, m, rows); break;
             }
-            dv = fabs(dv);
+          } else {
+            if (pt) {
+              const double eq = 1.0 / fmax(1.0, fabs(yl));
+              double t0 = 1.0, t1 = wl;
+              for (int k = 0; k < nn; ++k) {  // se < nn
+                if (k < nn) S.A[lane][k] = t0 * eq;
+                if (k < se) S.A[lane][nn + k] = -yl * t0 * eq;
+                if (k == se) S.A[lane][nc] = yl * t0 * eq;
+                const double t2 = 2.0 * wl * t1 - t0;
+                t0 = t1;
+                t1 = t2;
+              }
+            }
+            __syncthreads();
+            wave_least_squares(S, nfin, nc, lane);
+            // |D(w_i)|: every corrupted point is a root of every solution's locator polynomial
+            if (pt) {
+              double t0 = 1.0, t1 = wl;
+              for (int k = 0; k <= se; ++k) {
+                dv = fma(k < se ? S.x[nn + k] : 1.0, t0, dv);
+                const double t2 = 2.0 * wl * t1 - t0;
+                t0 = t1;
+                t1 = t2;
+              }
+              dv = fabs(dv);
+            }
           }
-          drank = wave_rank(dv, pt, nfin, lane);
+          drank = wave_rank(S.x, dv, pt, nfin, lane);
         }
         // V: the smallest set of points without which the rest is consistent (leading roots first, then wider)
         test_ctx tc;
@@ -748,8 +886,9 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
   if (st == SOLON_OK) {
     bool taken = false;
     double prod = fabs(wi);  // first pick: largest |w|
+    const int rows_g = n <= 16 ? 1 : n <= 32 ? 2 : 4;
     for (int t = 0; t < m; ++t) {
-      const int sel = wave_argmax(prod, honest && !taken, lane);  // largest product, lowest lane on ties; nh >= m: never -1
+      const int sel = wave_argmax(prod, honest && !taken, lane, rows_g);  // largest product, lowest lane on ties; nh >= m: never -1
       if (lane == sel) taken = true;
       const double dist = fabs(wi - lane_bcast(wi, sel));
       prod = (t == 0) ? dist : prod * dist;
@@ -769,21 +908,23 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
       if (__ballot(differs) && lane == 0) *a.redo = 1;
     }
     __syncthreads();
-    if (taken) {
-      double* poly = S.lag[tpos];
-      poly[0] = 1.0;
-      int deg = 0;
+    if (taken) {  // this lane's Lagrange basis polynomial: prod over the other chosen points of (w - w_u) / (w_t - w_u)
+      double poly[SOLON_MAX_M];
+#pragma unroll
+      for (int l = 0; l < SOLON_MAX_M; ++l) poly[l] = l == 0 ? 1.0 : 0.0;
       double den = 1.0;
       for (int u = 0; u < m; ++u) {
-        if (u == tpos) continue;
         const double wu = S.val[u];
-        poly[deg + 1] = 0.0;
-        for (int l = deg + 1; l >= 1; --l) poly[l] = poly[l - 1] - wu * poly[l];  // multiply by (w - w_u)
-        poly[0] = -wu * poly[0];
-        ++deg;
-        den *= (wi - wu);
+        if (u != tpos) {  // multiply by (w - w_u); coefficients above the current degree are zero and stay zero
+#pragma unroll
+          for (int l = SOLON_MAX_M - 1; l >= 1; --l) poly[l] = fma(-wu, poly[l], poly[l - 1]);
+          poly[0] = -wu * poly[0];
+          den *= (wi - wu);
+        }
       }
-      for (int l = 0; l < m; ++l) poly[l] /= den;
+      const double inv_den = 1.0 / den;
+#pragma unroll
+      for (int l = 0; l < SOLON_MAX_M; ++l) S.lag[tpos][l] = poly[l] * inv_den;
     }
     __syncthreads();
     double rowsum = 0.0;

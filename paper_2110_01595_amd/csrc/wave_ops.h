@@ -31,3 +31,38 @@ __device__ __forceinline__ double wave_sum_all(double v) {
   const int hi = __builtin_amdgcn_readlane(__double2hiint(t), 63);
   return __hiloint2double(hi, lo);
 }
+
+// N sums at once over the lanes of the first `rows` rows of 16 lanes (rows = 1, 2 or 4, wave-uniform; the other lanes are
+// ignored), identical bits in every lane.  The N reductions go through each permutation step together, so that their
+// dependent chains hide one another's latency: a lone wavefront sum is latency-bound, N of them cost little more.
+template <int N>
+__device__ __forceinline__ void wave_sums(double (&v)[N], int rows) {
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dpp_add<0xB1, 0xF>(v[i]);
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dpp_add<0x4E, 0xF>(v[i]);
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dpp_add<0x141, 0xF>(v[i]);
+#pragma unroll
+  for (int i = 0; i < N; ++i) v[i] = dpp_add<0x140, 0xF>(v[i]);
+  if (rows > 1) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = dpp_add<0x142, 0xA>(v[i]);
+  }
+  if (rows > 2) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = dpp_add<0x143, 0xC>(v[i]);
+  }
+  const int src = __builtin_amdgcn_readfirstlane(rows * 16 - 1);
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v[i]), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v[i]), src);
+    v[i] = __hiloint2double(hi, lo);
+  }
+}
+__device__ __forceinline__ double wave_sum_rows(double x, int rows) {
+  double v[1] = {x};
+  wave_sums<1>(v, rows);
+  return v[0];
+}
