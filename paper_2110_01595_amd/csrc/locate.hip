@@ -320,51 +320,57 @@ __device__ double locator_abs_values(double wl, double yl, bool pt, int m, int r
       t1 = t2;
     }
   }
-  double p_prev = 0.0, p_cur;
+  // One round of wavefront sums per degree: the next basis polynomial enters it UNNORMALISED (t, with |t|^2 among the
+  // sums) and every other sum of the round is scaled afterwards, so that no sum has to wait for a norm.
+  double p_cur = 0.0, t = eq;  // t: the polynomial of the current degree before normalisation
   {
     double v[SE + 2];
 #pragma unroll
     for (int k = 0; k <= SE; ++k) v[k] = c[k] * c[k];
-    v[SE + 1] = eq * eq;
+    v[SE + 1] = 0.0;
     wave_sums<SE + 2>(v, rows);
 #pragma unroll
     for (int k = 0; k <= SE; ++k) cn0[k] = sqrt(v[k]);
-    p_cur = eq / sqrt(v[SE + 1]);
   }
   const int nn = m + SE;
   for (int j = 0; j < nn; ++j) {
-    const double xp = wl * p_cur;
-    double v[SE + 3];
+    const double xt = wl * t;
+    double v[SE + 4];
 #pragma unroll
-    for (int k = 0; k <= SE; ++k) v[k] = c[k] * p_cur;
-    v[SE + 1] = xp * p_cur;
-    v[SE + 2] = xp * p_prev;
-    wave_sums<SE + 3>(v, rows);
+    for (int k = 0; k <= SE; ++k) v[k] = c[k] * t;
+    v[SE + 1] = t * t;
+    v[SE + 2] = xt * t;
+    v[SE + 3] = xt * p_cur;
+    wave_sums<SE + 4>(v, rows);
+    const double n2 = v[SE + 1];
+    if (!(n2 > 1e-300)) break;  // fewer distinct weighted points than coefficients: nothing further to remove
+    const double inv = 1.0 / sqrt(n2);
+    const double p_new = t * inv;  // orthonormal polynomial of degree j
 #pragma unroll
-    for (int k = 0; k <= SE; ++k) c[k] = fma(-v[k], p_cur, c[k]);
-    if (j + 1 == nn) break;
-    const double q = xp - v[SE + 1] * p_cur - v[SE + 2] * p_prev;
-    const double nrm = sqrt(wave_sum_rows(q * q, rows));
-    p_prev = p_cur;
-    p_cur = nrm > 1e-150 ? q / nrm : 0.0;
+    for (int k = 0; k <= SE; ++k) c[k] = fma(-v[k] * inv, p_new, c[k]);
+    // x p_new = (next) + alpha p_new + beta p_cur with alpha = <x p_new, p_new>, beta = <x p_new, p_cur>
+    t = wl * p_new - (v[SE + 2] * inv * inv) * p_new - (v[SE + 3] * inv) * p_cur;
+    p_cur = p_new;
   }
-  // Gram-Schmidt on what is left of the locator columns; a column that has (numerically) nothing left is dependent on
-  // the earlier ones and gets coefficient zero, which picks one of the system's solutions (Lemma l9, case ii)
+  // Gram-Schmidt on what is left of the locator columns (norm and dot products of a column in one round); a column
+  // that has (numerically) nothing left is dependent on the earlier ones and gets coefficient zero, which picks one of
+  // the system's solutions (Lemma l9, case ii)
   double r[SE][SE + 1];
   bool dep[SE];
 #pragma unroll
   for (int k = 0; k < SE; ++k) {
-    const double nk = sqrt(wave_sum_rows(c[k] * c[k], rows));
-    dep[k] = !(nk > SOLON_RANK_TOL * cn0[k]);
-    const double qk = dep[k] ? 0.0 : c[k] / nk;
-    r[k][k] = nk;
-    double v[SE];
+    double v[SE + 1];
 #pragma unroll
-    for (int j = 1; j <= SE; ++j) v[j - 1] = j > k ? qk * c[j] : 0.0;
-    wave_sums<SE>(v, rows);
+    for (int j = 0; j <= SE; ++j) v[j] = j >= k ? c[k] * c[j] : 0.0;
+    wave_sums<SE + 1>(v, rows);
+    const double nk = sqrt(v[k]);
+    dep[k] = !(nk > SOLON_RANK_TOL * cn0[k]);
+    const double ink = dep[k] ? 0.0 : 1.0 / nk;
+    const double qk = c[k] * ink;
+    r[k][k] = nk;
 #pragma unroll
     for (int j = k + 1; j <= SE; ++j) {
-      r[k][j] = v[j - 1];
+      r[k][j] = v[j] * ink;
       c[j] = fma(-r[k][j], qk, c[j]);
     }
   }
@@ -492,24 +498,22 @@ __device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m,
   const int rows = n <= 16 ? 1 : n <= 32 ? 2 : 4;
   const double wgt = pt ? 1.0 : 0.0;
   const double yc = fmin(fmax(y, -SOLON_Y_CLAMP), SOLON_Y_CLAMP);
-  double p_prev = 0.0, p_cur = wgt / sqrt((double)n), fit = 0.0;
+  double p_cur = 0.0, t = wgt, fit = 0.0;  // t: the polynomial of the current degree before normalisation
   double q[MM];
 #pragma unroll
   for (int k = 0; k < MM; ++k) q[k] = 0.0;
 #pragma unroll
   for (int k = 0; k < MM; ++k) {
-    if (k < m) {  // wave-uniform
-      q[k] = p_cur;
-      const double xp = x * p_cur;
-      double v[3] = {yc * p_cur, xp * p_cur, xp * p_prev};
-      wave_sums<3>(v, rows);
-      fit = fma(v[0], p_cur, fit);
-      if (k + 1 < m) {
-        const double t = xp - v[1] * p_cur - v[2] * p_prev;
-        const double nrm = sqrt(wave_sum_rows(t * t, rows));
-        p_prev = p_cur;
-        p_cur = nrm > 1e-150 ? t / nrm : 0.0;  // fewer distinct points than coefficients cannot happen (n >= m + s)
-      }
+    if (k < m) {  // wave-uniform; one round of sums per degree, scaled by the norm afterwards
+      const double xt = x * t;
+      double v[4] = {t * t, yc * t, xt * t, xt * p_cur};
+      wave_sums<4>(v, rows);
+      const double inv = v[0] > 1e-300 ? 1.0 / sqrt(v[0]) : 0.0;  // fewer distinct points than coefficients cannot happen (n >= m + s)
+      const double p_new = t * inv;
+      q[k] = p_new;
+      fit = fma(v[1] * inv, p_new, fit);
+      t = x * p_new - (v[2] * inv * inv) * p_new - (v[3] * inv) * p_cur;
+      p_cur = p_new;
     }
   }
   __syncthreads();  // S.A, S.val are free again
@@ -557,7 +561,11 @@ __device__ bool lane_test(const solve_smem& S, unsigned long long mask, int n) {
     for (int k = 0; k < j; ++k) d = fma(-L[j * (j + 1) / 2 + k], L[j * (j + 1) / 2 + k], d);
     const bool good = d > SOLON_CHOL_MIN;  // false for NaN too
     ok = ok && good;
-    inv[j] = 1.0 / sqrt(good ? d : 1.0);
+    const double dd = good ? d : 1.0;
+    double rs = __builtin_amdgcn_rsq(dd);  // hardware estimate, then two Newton steps: full double precision
+    rs = rs * fma(-0.5 * dd * rs, rs, 1.5);
+    rs = rs * fma(-0.5 * dd * rs, rs, 1.5);
+    inv[j] = rs;
 #pragma unroll
     for (int i = j + 1; i < E; ++i) {
       double t = L[i * (i + 1) / 2 + j];
@@ -581,6 +589,7 @@ __device__ bool lane_test(const solve_smem& S, unsigned long long mask, int n) {
     for (int c = a + 1; c < E; ++c) t = fma(-L[c * (c + 1) / 2 + a], dl[c], t);
     dl[a] = t * inv[a];
   }
+#pragma unroll 4
   for (int k = 0; k < n; ++k) {
     double res = S.val[k];
 #pragma unroll
