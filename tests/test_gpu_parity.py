@@ -22,15 +22,24 @@ def say(*a):
     print(*a, flush=True)
 
 
+def u_tol_for(m):
+    """Bar on the decoded aggregate's rel-L2 error: 1e-4 up to m = 11.  Beyond that the monomial code on an fp32 wire
+    is itself less accurate (the oracle's fp64 decode of the same messages leaves 5e-5 at m = 12 and 1.4e-3 at m = 16; the
+    paper reports the same wall, on its fp64 wire, beyond r_c = 14): two to four times the HIP path's measured worst case, so that the
+    element-wise bound (8 x the bar) covers the worst coordinate measured as well."""
+    return {12: 2.5e-4, 13: 7.5e-4, 14: 1.5e-3, 15: 5e-3, 16: 5e-3}.get(m, 1e-4)
+
+
 def host(t):
     return t.float().cpu().numpy()
 
 
 def run_case(P, s, m, d, dtype="f32", attack="flip10", byz=None, n_byz=None, seed=0, dist="normal", sigma=0.01,
-             check_bruteforce=None, u_tol=1e-4, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False,
+             check_bruteforce=None, u_tol=None, group_of_node=None, group_of_batch=None, w=None, B=None, pad=0, decode_from_host=False,
              fused=False, attack_from_column=0):
     """One encode -> attack -> locate -> decode round, compared step by step with the oracle."""
     say("case", dict(P=P, s=s, m=m, d=d, dtype=dtype, attack=attack, byz=byz, seed=seed, pad=pad))
+    u_tol = u_tol_for(m) if u_tol is None else u_tol
     cfg = dict(P=(P if B is None else B), d=d, dtype=dtype, dist=dist, sigma=sigma, mu_sigma=0.03)
     plan = solon.Plan(P, s, m, d, B=B, dtype=solon.SOLON_BF16 if dtype == "bf16" else solon.SOLON_F32,
                       group_of_node=group_of_node, group_of_batch=group_of_batch, w=w)
@@ -121,10 +130,12 @@ def test_round_fp32(P, s, m, d):
 
 
 def test_largest_compiled_compression_ratio():
-    """m = 16 runs through every kernel; its monomial Vandermonde is so ill-conditioned (the paper reports
-    numerical trouble beyond r_c = 14) that fp32 messages only support a looser bar on u."""
-    run_case(64, 0, 16, 70_000, seed=80, u_tol=5e-3)
-    run_case(40, 1, 12, 36_000, seed=81, u_tol=5e-3)
+    """m = 12 ... 16 run through every kernel; their monomial Vandermonde is so ill-conditioned (the paper reports
+    numerical trouble beyond r_c = 14) that fp32 messages only support the looser bars of u_tol_for."""
+    run_case(64, 0, 16, 70_000, seed=80)
+    run_case(40, 1, 12, 36_000, seed=81)
+    run_case(46, 3, 14, 56_000, attack="paper", seed=82)
+    run_case(52, 5, 16, 64_000, attack="mix", seed=83)
 
 
 @pytest.mark.parametrize("P,s,m,d", [(7, 1, 1, 20_001), (15, 1, 2, 40_002), (100, 5, 4, 33_001), (63, 3, 4, 40_008), (20, 2, 5, 25_003),
@@ -179,7 +190,7 @@ def test_phase_separated_kernels(grid):
         run_case(24, 2, 8, 70_001, seed=33)                                    # fp32: 8 does not divide four
         run_case(20, 2, 5, 60_003, dtype="bf16", seed=34)
         run_case(100, 5, 10, 150_010, dtype="bf16", attack="mix", dist="student3", sigma=1e-3, seed=35)
-        run_case(64, 0, 16, 70_000, seed=36, u_tol=5e-3)
+        run_case(64, 0, 16, 70_000, seed=36)
         gon = [0] * 5 + [-1] + [1] * 6                                          # an idle node: its row stays untouched
         run_case(12, 1, 2, 50_000, group_of_node=gon, group_of_batch=[0] * 6 + [1] * 6, seed=29)
     finally:
