@@ -138,13 +138,25 @@ int solon_locate(solon_plan* plan, const float* R, int64_t ldr, const float* f, 
  *   u[p m + l] = sum_g sum_t T[g][l][t] * R[U_g[t]][p],
  * where U_g holds m honest nodes of group g and T[g] is the inverse of their m x m Vandermonde.
  * Reads q * m rows of R, writes u once.
- *   byz_idx, n_byz  host: the located set to exclude, ascending global indices; or byz_idx == NULL and
- *                   n_byz < 0 to use what the preceding solon_locate on this plan left on the device
- *                   (no host round trip)
+ *   byz_idx, n_byz  host: the located set to exclude, ascending global indices (byz_idx == NULL with n_byz == 0: the
+ *                   empty set); or byz_idx == NULL and n_byz < 0 to use what the preceding solon_locate on this plan left
+ *                   on the device (no host round trip)
  *   u               device, d fp32
  */
 int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
                  void* hip_stream);
+
+/*
+ * solon_decode fused with the step that follows it in training (Sec. 3.1, "Distributed learning":
+ * w_t = w_{t-1} - gamma_t / |S_t| * sum of the gradients): the aggregate u = G 1_P is not written; every coordinate of
+ * the parameter vector is read, reduced by step * u[c] and written back by the recombination kernels themselves.
+ *   params  device, d fp32, updated in place
+ *   step    gamma / |S|: learning rate over the number of per-batch gradients in the sum
+ *   R, byz_idx, n_byz as for solon_decode.  Not idempotent: run it once per located round (check solon_decode_status of
+ *   the locate call first when the status matters; an update from a failed group is as unspecified as u would be).
+ */
+int solon_decode_update(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* params,
+                        float step, void* hip_stream);
 
 /*
  * solon_locate followed by solon_decode, in one pass over R (same paper passages; same V, same status, u to the same

@@ -26,6 +26,7 @@ Functions and the passage each follows
                      only to tie locate_bw to the printed formula on tiny well-conditioned cases
   decode             Algorithm 1 with psi = least-squares inverse of the honest rows'
                      Vandermonde (Sec. 3.4, Lemma 2); u = sum over groups
+  decode_update      decode followed by the training step w <- w - gamma / |S| * u (Sec. 3.1)
   plain_sum          the definition the whole mechanism must reproduce: G 1_P (Def. 1)
 
 Pins (tests/test_oracle_*.py): decode == plain_sum with zero and with <= s corrupted rows (Def. 1,
@@ -393,6 +394,13 @@ def decode(plan, R, V, d):
         coeffs = np.linalg.lstsq(W_U, R_U, rcond=None)[0]                   # m x d_c: chunk p's coefficients
         u += coeffs.T.reshape(-1)                                           # vec(): coordinate p m + l
     return u[:d]
+
+
+def decode_update(plan, R, V, params, step):
+    """The step that follows the path in training (Sec. 3.1, "Distributed learning"): w_t = w_{t-1} - gamma_t / |S_t| *
+    (sum of the gradients), with the sum recovered by decode() and step = gamma / |S|.  Returns the new parameters."""
+    params = np.asarray(params, dtype=np.float64)
+    return params - float(step) * decode(plan, R, V, params.shape[0])
 
 
 def decode_majority(plan, R, d):

@@ -2,6 +2,9 @@
 //   u[p m + l] = sum_g sum_t T[g][l][t] * R[U_g[t]][p]
 // with U_g the m honest nodes chosen for group g and T[g] the inverse of their m x m Vandermonde,
 // both left in the plan's workspace by the locator wavefront.  Reads q m rows of R once, writes u once.
+// Every kernel can instead apply the step that follows the path in training (paper Sec. 3.1, "Distributed learning":
+// w <- w - gamma / |S| * sum of the gradients): with `update` set, `u` points at the parameters and each coordinate is
+// read, reduced by step * (its recombined value) and written back, so the aggregate never makes a round trip through HBM.
 #include "grid_phase.h"
 #include "solon_internal.h"
 
@@ -18,7 +21,8 @@ template <> struct chunk_vec<4> { typedef f32x4 type; };
 template <int M, int CH, bool VEC>
 __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict__ R, int64_t ldr, int q, const int32_t* __restrict__ rows,
                                                          const float* __restrict__ coef, float* __restrict__ u, int64_t d,
-                                                         int64_t d_c, int64_t p_begin, const int32_t* __restrict__ run_flag) {
+                                                         int64_t d_c, int64_t p_begin, const int32_t* __restrict__ run_flag, float step,
+                                                         int update) {
   if (run_flag && *run_flag == 0) return;  // a speculative recombination already produced u
   const int64_t nunits = (d_c + CH - 1) / CH;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -56,12 +60,13 @@ __global__ __launch_bounds__(256) void recombine_kernel(const float* __restrict_
 #pragma unroll
       for (int i = 0; i < CH * M; i += 4) {
         f32x4 x = {out[i], out[i + 1], out[i + 2], out[i + 3]};
+        if (update) x = *reinterpret_cast<const f32x4*>(dst + i) - step * x;
         __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(dst + i));
       }
     } else {
 #pragma unroll
       for (int i = 0; i < CH * M; ++i)
-        if (p * M + i < d) dst[i] = out[i];  // the last chunk may reach past d
+        if (p * M + i < d) dst[i] = update ? dst[i] - step * out[i] : out[i];  // the last chunk may reach past d
     }
   }
 }
@@ -77,7 +82,7 @@ template <int M>
 __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* __restrict__ R, int64_t ldr, int q,
                                                                    const int32_t* __restrict__ rows, const float* __restrict__ coef,
                                                                    float* __restrict__ u, int64_t nunits, uint32_t* sync, int spin_limit,
-                                                                   const int32_t* __restrict__ run_flag) {
+                                                                   const int32_t* __restrict__ run_flag, float step, int update) {
   if (run_flag && *run_flag == 0) return;  // every block leaves before the first alignment point: the counters stay zero
   constexpr int CH = 4 / M;
   constexpr int U = recombine_phase_units(M);
@@ -129,6 +134,7 @@ __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* _
       const uint32_t unit = u0 + (uint32_t)i * span;
       if (unit <= last) {
         f32x4 o = {out[i][0], out[i][1], out[i][2], out[i][3]};
+        if (update) o = *reinterpret_cast<const f32x4*>(u + (int64_t)unit * 4) - step * o;
         __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(u + (int64_t)unit * 4));
       }
     }
@@ -143,7 +149,8 @@ __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* _
 template <int M>
 __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __restrict__ R, int64_t ldr, int q,
                                                               const int32_t* __restrict__ rows, const float* __restrict__ coef,
-                                                              float* __restrict__ u, const int32_t* __restrict__ run_flag) {
+                                                              float* __restrict__ u, const int32_t* __restrict__ run_flag, float step,
+                                                              int update) {
   if (run_flag && *run_flag == 0) return;
   __shared__ float tile_out[256 * M];
   const int tid = threadIdx.x;
@@ -164,12 +171,16 @@ __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __rest
   for (int l = 0; l < M; ++l) tile_out[tid * M + l] = out[l];
   __syncthreads();
   float* dst = u + tile * (256 * M);
-  for (int v = tid; v < 64 * M; v += 256)
-    __builtin_nontemporal_store(*reinterpret_cast<const f32x4*>(&tile_out[4 * v]), reinterpret_cast<f32x4*>(dst + 4 * v));
+  for (int v = tid; v < 64 * M; v += 256) {
+    f32x4 x = *reinterpret_cast<const f32x4*>(&tile_out[4 * v]);
+    if (update) x = *reinterpret_cast<const f32x4*>(dst + 4 * v) - step * x;
+    __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(dst + 4 * v));
+  }
 }
 
 template <int M, int CH = ((M % 4 == 0) ? 1 : (M % 2 == 0 ? 2 : 4))>  // CH * M is a multiple of four
-static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st) {
+static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st, float step,
+                              int update) {
   // CH-float loads from the rows of R and 16-byte stores of u
   const bool vec = ((uintptr_t)R % (4 * CH) == 0) && (ldr % CH == 0) && ((uintptr_t)u % 16 == 0);
   const int cap = solon_tuning("decode_blocks", 1 << 22);
@@ -178,7 +189,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
     const int64_t ntiles = plan->d / (256 * M);  // tiles that lie entirely below d
     if (ntiles > 0 && (uintptr_t)u % 16 == 0 && solon_tuning("decode_force_generic", 0) == 0) {
       hipLaunchKernelGGL((recombine_tile_kernel<M>), dim3((unsigned)ntiles), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u, run_flag);
+                         plan->dev.dec_coef, u, run_flag, step, update);
       SOLON_HIP(hipGetLastError());
       p_begin = ntiles * 256;
     }
@@ -198,7 +209,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
     }
     if (phase_grid > 0) {
       hipLaunchKernelGGL((recombine_phase_kernel<M>), dim3((unsigned)phase_grid), dim3(1024), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), run_flag);
+                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), run_flag, step, update);
       SOLON_HIP(hipGetLastError());
       p_begin = punits * PCH;  // a multiple of every CH used below
     }
@@ -209,10 +220,10 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
   blocks = std::max<int64_t>(blocks, 1);
   if (vec)
     hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag, step, update);
   else
     hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_begin, run_flag, step, update);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
@@ -225,10 +236,10 @@ static int recombine_from(const solon_plan* plan, const float* R, int64_t ldr, f
   const int64_t blocks = std::max<int64_t>(1, (nunits + 255) / 256);
   if (vec)
     hipLaunchKernelGGL((recombine_kernel<M, CH, true>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr, 0.0f, 0);
   else
     hipLaunchKernelGGL((recombine_kernel<M, CH, false>), dim3((unsigned)blocks), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr);
+                       plan->dev.dec_coef, u, plan->d, plan->d_c, p_start, (const int32_t*)nullptr, 0.0f, 0);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }
@@ -244,14 +255,15 @@ int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t 
   return SOLON_E_INVAL;
 }
 
-int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st) {
+int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st, float step,
+                           int update) {
   if (plan->m == 4) {  // chunks per thread: two measured best on C4 / C5 (0.68 vs 0.70 ms with one, 0.95 ms with four)
     const int ch = solon_tuning("decode_ch", 2);
-    if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, run_flag, st);
-    if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, run_flag, st);
+    if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, run_flag, st, step, update);
+    if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, run_flag, st, step, update);
   }
   switch (plan->m) {
-#define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, run_flag, st);
+#define SOLON_CASE(MV) case MV: return recombine_dispatch<MV>(plan, R, ldr, u, run_flag, st, step, update);
     SOLON_CASE(1) SOLON_CASE(2) SOLON_CASE(3) SOLON_CASE(4) SOLON_CASE(5) SOLON_CASE(6) SOLON_CASE(7) SOLON_CASE(8)
     SOLON_CASE(9) SOLON_CASE(10) SOLON_CASE(11) SOLON_CASE(12) SOLON_CASE(13) SOLON_CASE(14) SOLON_CASE(15) SOLON_CASE(16)
 #undef SOLON_CASE
@@ -260,53 +272,67 @@ int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, 
   return SOLON_E_INVAL;
 }
 
-extern "C" int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
-                            void* hip_stream) {
-  if (!plan || !R || !u) {
-    solon_set_error("solon_decode: null argument");
+// psi's tables for the located set: either the caller names it (host list) or the preceding locate left it on the device
+static int prepare_decode(const char* who, solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, const float* out,
+                          hipStream_t st) {
+  if (!plan || !R || !out) {
+    solon_set_error("%s: null argument", who);
     return SOLON_E_INVAL;
   }
   if (ldr < plan->d_c) {
-    solon_set_error("solon_decode: ldr %lld < d_c %lld", (long long)ldr, (long long)plan->d_c);
+    solon_set_error("%s: ldr %lld < d_c %lld", who, (long long)ldr, (long long)plan->d_c);
     return SOLON_E_INVAL;
   }
   if (!plan->ws) {
-    solon_set_error("solon_decode: the plan has no device workspace (no GPU at creation)");
+    solon_set_error("%s: the plan has no device workspace (no GPU at creation)", who);
     return SOLON_E_HIP;
   }
-  hipStream_t st = (hipStream_t)hip_stream;
-  if (n_byz >= 0) {
-    // the caller names the located set: rebuild psi's tables for it on the device
-    if (n_byz > 0 && !byz_idx) {
-      solon_set_error("solon_decode: n_byz > 0 with a null index list");
-      return SOLON_E_INVAL;
-    }
-    SOLON_HIP(hipStreamSynchronize(st));  // the staging buffer may still be in use by an earlier call on this stream
-    int32_t* h_vmask = (int32_t*)plan->pinned;
-    std::vector<int> per_group(plan->q, 0);
-    for (int j = 0; j < plan->P; ++j) h_vmask[j] = 0;
-    for (int i = 0; i < n_byz; ++i) {
-      const int j = byz_idx[i];
-      if (j < 0 || j >= plan->P) {
-        solon_set_error("solon_decode: located index %d outside [0, %d)", j, plan->P);
-        return SOLON_E_INVAL;
-      }
-      if (!h_vmask[j] && plan->group_of_node[j] >= 0) per_group[plan->group_of_node[j]]++;
-      h_vmask[j] = 1;
-    }
-    for (int g = 0; g < plan->q; ++g) {
-      const int n = plan->grp_off[g + 1] - plan->grp_off[g];
-      if (n - per_group[g] < plan->m) {
-        solon_set_error("solon_decode: group %d keeps fewer than m = %d nodes", g, plan->m);
-        return SOLON_E_DECODE;
-      }
-    }
-    SOLON_HIP(hipMemcpyAsync(plan->dev.vmask, h_vmask, sizeof(int32_t) * plan->P, hipMemcpyHostToDevice, st));
-    int rc = solon_launch_solve(plan, SOLVE_TABLES, st);
-    if (rc != SOLON_OK) return rc;
-  } else if (byz_idx) {
-    solon_set_error("solon_decode: n_byz < 0 requires a null index list");
+  if (!byz_idx && n_byz > 0) {
+    solon_set_error("%s: n_byz > 0 with a null index list", who);
     return SOLON_E_INVAL;
   }
+  if (!byz_idx && n_byz < 0) return SOLON_OK;  // the preceding solon_locate's result, still on the device
+  if (n_byz < 0) {
+    solon_set_error("%s: n_byz < 0 requires a null index list", who);
+    return SOLON_E_INVAL;
+  }
+  // the caller names the located set: rebuild psi's tables for it on the device
+  SOLON_HIP(hipStreamSynchronize(st));  // the staging buffer may still be in use by an earlier call on this stream
+  int32_t* h_vmask = (int32_t*)plan->pinned;
+  std::vector<int> per_group(plan->q, 0);
+  for (int j = 0; j < plan->P; ++j) h_vmask[j] = 0;
+  for (int i = 0; i < n_byz; ++i) {
+    const int j = byz_idx[i];
+    if (j < 0 || j >= plan->P) {
+      solon_set_error("%s: located index %d outside [0, %d)", who, j, plan->P);
+      return SOLON_E_INVAL;
+    }
+    if (!h_vmask[j] && plan->group_of_node[j] >= 0) per_group[plan->group_of_node[j]]++;
+    h_vmask[j] = 1;
+  }
+  for (int g = 0; g < plan->q; ++g) {
+    const int n = plan->grp_off[g + 1] - plan->grp_off[g];
+    if (n - per_group[g] < plan->m) {
+      solon_set_error("%s: group %d keeps fewer than m = %d nodes", who, g, plan->m);
+      return SOLON_E_DECODE;
+    }
+  }
+  SOLON_HIP(hipMemcpyAsync(plan->dev.vmask, h_vmask, sizeof(int32_t) * plan->P, hipMemcpyHostToDevice, st));
+  return solon_launch_solve(plan, SOLVE_TABLES, st);
+}
+
+extern "C" int solon_decode(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* u,
+                            void* hip_stream) {
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int rc = prepare_decode("solon_decode", plan, R, ldr, byz_idx, n_byz, u, st);
+  if (rc != SOLON_OK) return rc;
   return solon_launch_recombine(plan, R, ldr, u, nullptr, st);
+}
+
+extern "C" int solon_decode_update(solon_plan* plan, const float* R, int64_t ldr, const int32_t* byz_idx, int32_t n_byz, float* params,
+                                   float step, void* hip_stream) {
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int rc = prepare_decode("solon_decode_update", plan, R, ldr, byz_idx, n_byz, params, st);
+  if (rc != SOLON_OK) return rc;
+  return solon_launch_recombine(plan, R, ldr, params, nullptr, st, step, 1);
 }

@@ -94,7 +94,9 @@ int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, 
 // waits for the stream, copies status (and optionally the located mask and rho) to the host, returns the worst group status
 int solon_collect_status(solon_plan* plan, hipStream_t st, int32_t* vmask_host, double* rho_host);
 // run_flag: device int32 or null; when it points at 0 the kernels return at once (u already holds the result)
-int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st);
+// update != 0: u points at the parameters, which are reduced in place by step * (the recombined aggregate)
+int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st, float step = 0.0f,
+                           int update = 0);
 // chunks p_start .. d_c - 1 only (p_start a multiple of four), with the general kernel
 int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t ldr, float* u, int64_t p_start, hipStream_t st);
 // asks for the device address of the library's static scratch array on the current device (kept per device)

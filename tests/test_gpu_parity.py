@@ -447,6 +447,49 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
         solon.solon_tune("fuse_sample", 1 << 17)
 
 
+@pytest.mark.parametrize("P,s,m,d,phase", [(63, 3, 4, 131_075, 1), (63, 3, 4, 40_004, 0), (15, 1, 2, 40_002, 1), (7, 1, 1, 70_001, 1),
+                                          (100, 5, 10, 50_010, 0), (20, 2, 5, 25_003, 0), (100, 5, 4, 33_001, 0)])
+def test_decode_fused_with_the_sgd_step(P, s, m, d, phase):
+    """solon_decode_update against the oracle's decode followed by w <- w - step * u (Sec. 3.1), through every
+    recombination kernel (flat, tiled, phase-separated): each parameter within one fp32 rounding of its own size plus
+    step times the bound that holds for u itself."""
+    say("update case", dict(P=P, s=s, m=m, d=d, phase=phase))
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    G = workloads.make_gradients(cfg, DEV, 500 + P, d=d)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    byz = workloads.pick_byzantine(P, s, 600 + P)
+    R = workloads.apply_attack(Z.clone(), byz, "mix", 700 + P)
+    f = workloads.make_projection(plan.d_c, DEV, 800 + P)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(900 + P)
+    w0 = torch.randn(d + 2, generator=gen, device=DEV, dtype=torch.float32)
+    step = 0.1 / P
+    solon.solon_tune("decode_phase", phase)
+    solon.solon_tune("decode_phase_grid", 3 if phase else 0)
+    try:
+        for host_set in (False, True):
+            params = w0.clone()
+            V, _ = solon.solon_locate(plan, R, f)
+            assert V == byz
+            solon.solon_decode_update(plan, R, params[:d], step, byz=V if host_set else None)
+            torch.cuda.synchronize()
+            assert torch.equal(params[d:], w0[d:])                      # nothing touched past the parameters
+            ref = so.decode_update(oplan, R.cpu().numpy(), V, w0[:d].cpu().numpy(), step)
+            u_ref = so.decode(oplan, R.cpu().numpy(), V, d)
+            rms = float(np.sqrt(np.mean(u_ref * u_ref)))
+            err = np.abs(params[:d].cpu().numpy().astype(np.float64) - ref)
+            bound = 2.0 ** -23 * np.abs(ref) + step * 8.0 * u_tol_for(m) * (np.abs(u_ref) + rms)
+            assert np.all(err <= bound), float((err / bound).max())
+            plain = w0[:d].cpu().numpy().astype(np.float64) - step * so.plain_sum(host(G))
+            assert so.rel_l2(params[:d].cpu().numpy(), plain) <= 1e-6
+    finally:
+        solon.solon_tune("decode_phase", -1)
+        solon.solon_tune("decode_phase_grid", 0)
+
+
 def test_degenerate_shapes():
     """No tolerance at all (s = 0: groups of m nodes, nothing to locate, psi inverts the group's own Vandermonde), the
     plain sum without code (s = 0, m = 1: every node its own group), a single group (P = r), one coordinate."""

@@ -184,6 +184,30 @@ def test_any_s_corruptions_are_located_and_removed(P, s, m, kind):
         assert so.rel_l2(u, so.plain_sum(G)) < 1e-9
 
 
+def test_update_is_the_plain_sgd_step_on_the_true_gradient_sum():
+    """Sec. 3.1: w_t = w_{t-1} - gamma / |S| * sum_k g_k, written as scalar loops over the TRUE gradients - whatever
+    up to s nodes sent instead."""
+    rng = np.random.default_rng(21)
+    P, s, m, d = 10, 3, 4, 37
+    plan = so.make_plan(P, s, m)
+    G = rand_G(rng, P, d)
+    Z = so.encode(plan, G)
+    w0 = rng.standard_normal(d)
+    gamma = 0.05
+    expect = np.empty(d)
+    for c in range(d):
+        total = 0.0
+        for k in range(P):
+            total += float(G[k, c])
+        expect[c] = w0[c] - gamma / P * total
+    for bad in ([], [0, 4, 9]):
+        R = corrupt(rng, Z, bad, "mix")
+        f = 1.0 + rng.standard_normal(Z.shape[1])
+        V = so.locate(plan, so.project(R, f), "bw")
+        assert V == bad
+        assert np.allclose(so.decode_update(plan, R, V, w0, gamma / P), expect, rtol=0, atol=1e-12)
+
+
 def test_colluding_valid_codeword_of_fake_gradient():
     """s nodes of one group send consistent messages of a different gradient: still out-voted."""
     rng = np.random.default_rng(5)
