@@ -115,6 +115,16 @@ int solon_default_points(int r_g, float* out);
 int solon_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, void* hip_stream);
 
 /*
+ * The projection vector of phi, drawn on the device (Sec. 3.4: f is generated inside phi, i.i.d. normal with mean one and
+ * unit variance): f[p] = 1 + z_p with z_p standard normal, a pure function of (seed, p) - Philox-4x32-10 on the counter
+ * (p / 4, 0, 0, 0) under the key (low, high word of seed), Box-Muller on the two word pairs in double precision, rounded to
+ * float once - so that a fresh f costs one call and no host traffic, and any implementation of the same recipe reproduces
+ * it.  Draw it AFTER R has arrived: a sender that knows f can hide a corruption from the projection.
+ *   f   device, d_c fp32 (written)
+ */
+int solon_draw_projection(uint64_t seed, int64_t d_c, float* f, void* hip_stream);
+
+/*
  * phi for all q groups (Sec. 3.4; Lemma 1): projections rho_j = sum_p f_p R[j][p] accumulated in fp64 with
  * a fixed reduction order, then per group the error-locator system
  *   [W_{m+s-1}, -W_{s-1} .* (rho 1^T)] a = rho .* w^s

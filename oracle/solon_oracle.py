@@ -17,6 +17,7 @@ Functions and the passage each follows
                      its corollary as parameter checks; ragged groups when r does not divide P
   default_points     "any distinct nonzero scalars" w_j (Sec. 3.4) - the values are this build's choice
   encode             z_j = W_j Y_j 1_P with W_j = I_{d_c} (x) [1, w_j, ..., w_j^{m-1}] (Sec. 3.4)
+  draw_projection    the random vector f of phi (Sec. 3.4), counter-based
   project            r_{j,c} = f R_j (Sec. 3.4, definition of phi)
   locate_bruteforce  the combinatorial definition: smallest subset S whose complement is
                      consistent with the code (App. C, sparse-recovery equivalence)
@@ -159,6 +160,43 @@ def encode(plan, G):
             powers = np.array([wj ** l for l in range(m)], dtype=np.float64)
             Z[j] = chunks @ powers                         # row p of W_j is [1, w_j, ..., w_j^{m-1}] on chunk p
     return Z
+
+
+def draw_projection(seed, d_c):
+    """f of phi (Sec. 3.4: i.i.d. normal, mean one, unit variance) as a pure function of (seed, column): the counter-based
+    recipe the library documents - Philox-4x32 with ten rounds (Salmon et al., SC 2011) on the counter (column // 4, 0, 0, 0)
+    under the key (seed mod 2^32, seed // 2^32); each pair of output words (x, y) gives the two normals
+    sqrt(-2 ln u1) (cos, sin)(2 pi u2), u1 = (x + 1/2) 2^-32, u2 = (y + 1/2) 2^-32, in double precision; f = 1 + z as float32."""
+    M0, M1, W0, W1 = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85
+    nq = -(-d_c // 4)
+    q = np.arange(nq, dtype=np.uint64)
+    c = [q & np.uint64(0xFFFFFFFF), q >> np.uint64(32), np.zeros(nq, np.uint64), np.zeros(nq, np.uint64)]
+    k0, k1 = int(seed) & 0xFFFFFFFF, (int(seed) >> 32) & 0xFFFFFFFF
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        p0 = np.uint64(M0) * c[0]                       # 32 x 32 -> 64 bit products (operands are below 2^32)
+        p1 = np.uint64(M1) * c[2]
+        c = [(p1 >> np.uint64(32)) ^ c[1] ^ np.uint64(k0), p1 & mask, (p0 >> np.uint64(32)) ^ c[3] ^ np.uint64(k1), p0 & mask]
+        k0, k1 = (k0 + W0) & 0xFFFFFFFF, (k1 + W1) & 0xFFFFFFFF
+    out = np.empty((nq, 4), dtype=np.float64)
+    for a, (x, y) in enumerate(((c[0], c[1]), (c[2], c[3]))):
+        u1 = (x.astype(np.float64) + 0.5) * 2.0 ** -32
+        u2 = (y.astype(np.float64) + 0.5) * 2.0 ** -32
+        r = np.sqrt(-2.0 * np.log(u1))
+        out[:, 2 * a] = 1.0 + r * np.cos(2.0 * np.pi * u2)
+        out[:, 2 * a + 1] = 1.0 + r * np.sin(2.0 * np.pi * u2)
+    return out.reshape(-1)[:d_c].astype(np.float32)
+
+
+def philox4x32_10(counter, key):
+    """One block of the generator above for a single counter (c0, c1, c2, c3) and key (k0, k1): four 32-bit words."""
+    c = [int(v) for v in counter]
+    k0, k1 = int(key[0]), int(key[1])
+    for _ in range(10):
+        p0, p1 = 0xD2511F53 * c[0], 0xCD9E8D57 * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k0, p1 & 0xFFFFFFFF, (p0 >> 32) ^ c[3] ^ k1, p0 & 0xFFFFFFFF]
+        k0, k1 = (k0 + 0x9E3779B9) & 0xFFFFFFFF, (k1 + 0xBB67AE85) & 0xFFFFFFFF
+    return c
 
 
 def project(R, f):

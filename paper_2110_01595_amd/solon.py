@@ -20,7 +20,7 @@ SOLON_Q_LAST_REDO, SOLON_Q_LIMIT_GROUP, SOLON_Q_LIMIT_M, SOLON_Q_LAST_ONE_PASS =
 EXPORTS = [
     "solon_plan_create", "solon_plan_destroy", "solon_plan_query", "solon_plan_groups", "solon_plan_points",
     "solon_default_points", "solon_encode", "solon_locate", "solon_decode", "solon_locate_decode", "solon_decode_majority",
-    "solon_decode_status", "solon_locate_static", "solon_decode_update",
+    "solon_decode_status", "solon_locate_static", "solon_decode_update", "solon_draw_projection",
     "solon_tune",
     "solon_last_error",
 ]
@@ -64,6 +64,8 @@ def lib():
     L.solon_locate.restype = i32
     L.solon_decode.argtypes = [vp, vp, i64, vp, i32, vp, vp]
     L.solon_decode.restype = i32
+    L.solon_draw_projection.argtypes = [ctypes.c_uint64, i64, vp, vp]
+    L.solon_draw_projection.restype = i32
     L.solon_decode_update.argtypes = [vp, vp, i64, vp, i32, vp, ctypes.c_float, vp]
     L.solon_decode_update.restype = i32
     L.solon_locate_decode.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
@@ -185,6 +187,12 @@ def solon_decode(plan, R, u, byz=None, stream=None):
     else:
         idx = np.ascontiguousarray(byz, dtype=np.int32)
         _check(lib().solon_decode(plan._h, _dev_ptr(R), R.stride(0), _np_ptr(idx), len(idx), _dev_ptr(u), _stream(stream)))
+
+
+def solon_draw_projection(seed, f, stream=None):
+    """Fills the fp32 CUDA tensor f with the projection vector of this seed (1 + standard normal, counter-based)."""
+    assert f.is_cuda and f.is_contiguous()
+    _check(lib().solon_draw_projection(ctypes.c_uint64(int(seed) & (2 ** 64 - 1)), f.numel(), _dev_ptr(f), _stream(stream)))
 
 
 def solon_decode_update(plan, R, params, step, byz=None, stream=None):

@@ -490,6 +490,39 @@ def test_decode_fused_with_the_sgd_step(P, s, m, d, phase):
         solon.solon_tune("decode_phase_grid", 0)
 
 
+@pytest.mark.parametrize("seed,n", [(0, 1), (1, 4099), (2 ** 63 + 12345, 1_000_003), ((0x9abcdef0 << 32) | 0x12345678, 262_144)])
+def test_projection_vector_drawn_on_the_device(seed, n):
+    """solon_draw_projection against the oracle's implementation of the same counter-based recipe: the same float for
+    (nearly) every column - both evaluate the transform in double precision and round once; where the two double results
+    straddle a rounding boundary the floats may differ by one unit in the last place."""
+    f = torch.full((n + 3,), 9.0, dtype=torch.float32, device=DEV)
+    solon.solon_draw_projection(seed, f[:n])
+    torch.cuda.synchronize()
+    assert bool((f[n:] == 9.0).all())
+    fh, ref = f[:n].cpu().numpy(), so.draw_projection(seed, n)
+    differ = np.flatnonzero(fh != ref)
+    assert differ.size <= max(1, n // 100_000), differ.size
+    assert np.all(np.abs(fh[differ] - ref[differ]) <= np.spacing(np.abs(ref[differ])))
+
+
+def test_round_with_a_projection_vector_drawn_on_the_device():
+    P, s, m, d = 63, 3, 4, 200_004
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    G = workloads.make_gradients(cfg, DEV, 31, d=d)
+    Z = torch.empty((P, plan.d_c), dtype=torch.float32, device=DEV)
+    solon.solon_encode(plan, G, Z)
+    byz = workloads.pick_byzantine(P, s, 32)
+    R = workloads.apply_attack(Z.clone(), byz, "mix", 33)
+    f = torch.empty(plan.d_c, dtype=torch.float32, device=DEV)
+    solon.solon_draw_projection(2024, f)
+    V, rho = solon.solon_locate(plan, R, f, want_rho=True)
+    rho_ref = so.project(R.cpu().numpy(), so.draw_projection(2024, plan.d_c))   # the oracle draws its own f
+    assert np.abs(rho - rho_ref).max() <= 1e-9 * np.abs(rho_ref).max()        # a handful of last-place differences in f at most
+    assert V == byz == so.locate(oplan, rho_ref, "bruteforce_stacked")
+
+
 def test_degenerate_shapes():
     """No tolerance at all (s = 0: groups of m nodes, nothing to locate, psi inverts the group's own Vandermonde), the
     plain sum without code (s = 0, m = 1: every node its own group), a single group (P = r), one coordinate."""

@@ -86,6 +86,36 @@ def test_message_length_table2():
     assert so.message_length(4099, 4) == 1025 and so.message_length(4096, 4) == 1024 and so.message_length(1, 4) == 1
 
 
+# ---------------------------------------------------------------- f of phi (Sec. 3.4), counter-based
+def test_generator_matches_the_published_known_answers():
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) == 3
+    for words in rows:
+        v = [int(x, 16) for x in words]
+        assert so.philox4x32_10(v[0:4], v[4:6]) == v[6:10]
+
+
+def test_drawn_projection_vector_is_the_documented_function_of_seed_and_column():
+    """Element p of f depends on (seed, p) only: the block generator on counter (p // 4, 0, 0, 0), Box-Muller on word pair
+    (p % 4) // 2 - checked element by element with scalar arithmetic; and f is N(1, 1) as Sec. 3.4 asks (first four moments)."""
+    import math
+    seed = (0x9abcdef0 << 32) | 0x12345678
+    f = so.draw_projection(seed, 1003)
+    assert f.shape == (1003,) and f.dtype == np.float32
+    for p in (0, 1, 2, 3, 4, 517, 1001, 1002):
+        x = so.philox4x32_10((p // 4, 0, 0, 0), (0x12345678, 0x9abcdef0))
+        a, b = x[2 * ((p % 4) // 2)], x[2 * ((p % 4) // 2) + 1]
+        r = math.sqrt(-2.0 * math.log((a + 0.5) / 2.0 ** 32))
+        ang = 2.0 * math.pi * (b + 0.5) / 2.0 ** 32
+        z = r * (math.cos(ang) if p % 2 == 0 else math.sin(ang))
+        assert abs(float(f[p]) - (1.0 + z)) <= 2.0 ** -22 * max(1.0, abs(1.0 + z))
+    assert np.array_equal(so.draw_projection(seed, 40)[:37], so.draw_projection(seed, 37))      # a prefix is a prefix
+    assert not np.array_equal(so.draw_projection(seed + 1, 40), so.draw_projection(seed, 40))
+    g = so.draw_projection(7, 2_000_000).astype(np.float64) - 1.0
+    assert abs(g.mean()) < 4e-3 and abs(g.var() - 1.0) < 6e-3 and abs((g ** 3).mean()) < 2e-2 and abs((g ** 4).mean() - 3.0) < 5e-2
+
+
 # ---------------------------------------------------------------- encode (Sec. 3.4)
 def test_encode_coordinatewise_definition():
     """Z[j][p] = sum_l w_j^l * (sum of the group's gradients)[p m + l], written as scalar loops."""
