@@ -346,11 +346,18 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
     float y[M];
 #pragma unroll
     for (int l = 0; l < M; ++l) y[l] = 0.0f;
+    // coordinates past d count as zero.  The rows' loads are independent of one another: four rows' worth are issued
+    // before the first is used (this kernel usually serves a ragged tail of a few hundred chunks, where nothing but the
+    // latency of these loads takes time)
+    const int nl = (int)((a.d - p * M) < M ? (a.d - p * M) : M);  // coefficients of this chunk that lie inside the row
+#pragma unroll 4
     for (int k = b0; k < b1; ++k) {
       const T* src = G + (int64_t)grp_batches[k] * a.ldg + p * M;
+      float v[M];
 #pragma unroll
-      for (int l = 0; l < M; ++l)
-        if (p * M + l < a.d) y[l] += elem_to_float(src[l]);  // coordinates past d count as zero
+      for (int l = 0; l < M; ++l) v[l] = l < nl ? elem_to_float(src[l]) : 0.0f;
+#pragma unroll
+      for (int l = 0; l < M; ++l) y[l] += v[l];
     }
     for (int t = n0; t < n1; ++t) {
       const int j = grp_nodes[t];
