@@ -149,20 +149,21 @@ __global__ __launch_bounds__(1024, 8) void recombine_phase_kernel(const float* _
 template <int M>
 __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __restrict__ R, int64_t ldr, int q,
                                                               const int32_t* __restrict__ rows, const float* __restrict__ coef,
-                                                              float* __restrict__ u, const int32_t* __restrict__ run_flag, float step,
-                                                              int update) {
+                                                              float* __restrict__ u, int64_t d, int64_t d_c,
+                                                              const int32_t* __restrict__ run_flag, float step, int update) {
   if (run_flag && *run_flag == 0) return;
   __shared__ float tile_out[256 * M];
   const int tid = threadIdx.x;
   const int64_t tile = blockIdx.x;
   const int64_t p = tile * 256 + tid;
+  const bool have = p < d_c;  // the last tile may be a partial one (d a multiple of four: no 16-byte store straddles the end)
   float out[M];
 #pragma unroll
   for (int l = 0; l < M; ++l) out[l] = 0.0f;
   for (int g = 0; g < q; ++g) {
 #pragma unroll
     for (int t = 0; t < M; ++t) {
-      const float v = __builtin_nontemporal_load(R + (int64_t)rows[g * M + t] * ldr + p);
+      const float v = have ? __builtin_nontemporal_load(R + (int64_t)rows[g * M + t] * ldr + p) : 0.0f;
 #pragma unroll
       for (int l = 0; l < M; ++l) out[l] = fmaf(coef[(g * M + t) * M + l], v, out[l]);
     }
@@ -172,6 +173,7 @@ __global__ __launch_bounds__(256) void recombine_tile_kernel(const float* __rest
   __syncthreads();
   float* dst = u + tile * (256 * M);
   for (int v = tid; v < 64 * M; v += 256) {
+    if (tile * (256 * M) + 4 * v >= d) break;
     f32x4 x = *reinterpret_cast<const f32x4*>(&tile_out[4 * v]);
     if (update) x = *reinterpret_cast<const f32x4*>(dst + 4 * v) - step * x;
     __builtin_nontemporal_store(x, reinterpret_cast<f32x4*>(dst + 4 * v));
@@ -186,12 +188,13 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
   const int cap = solon_tuning("decode_blocks", 1 << 22);
   int64_t p_begin = 0;
   if constexpr (M != 1 && M != 2 && M != 4) {
-    const int64_t ntiles = plan->d / (256 * M);  // tiles that lie entirely below d
+    // tiles that lie entirely below d, and the partial last one when d is a multiple of four
+    const int64_t ntiles = plan->d % 4 == 0 ? (plan->d + 256 * M - 1) / (256 * M) : plan->d / (256 * M);
     if (ntiles > 0 && (uintptr_t)u % 16 == 0 && solon_tuning("decode_force_generic", 0) == 0) {
       hipLaunchKernelGGL((recombine_tile_kernel<M>), dim3((unsigned)ntiles), dim3(256), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u, run_flag, step, update);
+                         plan->dev.dec_coef, u, plan->d, plan->d_c, run_flag, step, update);
       SOLON_HIP(hipGetLastError());
-      p_begin = ntiles * 256;
+      p_begin = std::min<int64_t>(ntiles * 256, plan->d_c);
     }
   }
   if constexpr (M == 1 || M == 2 || M == 4) {

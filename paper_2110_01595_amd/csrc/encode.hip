@@ -373,7 +373,8 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
 // Tiled path for compression ratios that do not divide the 16-byte load width.  A block owns 256 consecutive
 // chunks of one group (256 m coordinates): the group sum is accumulated position-wise with coalesced 16-byte
 // loads (that part does not depend on m), parked in LDS, and then each thread picks up the m coefficients of its
-// own chunk and writes one message element per node (coalesced 4-byte stores).
+// own chunk and writes one message element per node (coalesced 4-byte stores).  The last tile may be a partial one as
+// long as the row ends on a vector boundary: vectors past the row's end count as zero, chunks past d_c are not written.
 template <int M, typename T, bool NT>
 __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t tile0, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
@@ -386,18 +387,21 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t ti
   const int64_t tile = tile0 + blockIdx.x;
   const T* base = static_cast<const T*>(a.G) + tile * (256 * M);
   float acc[NI][LV];
+  bool inside[NI];  // this thread's vectors that lie inside the tile and inside the row
+  const int64_t row_vecs = a.d / LV - tile * NVEC;
 #pragma unroll
-  for (int i = 0; i < NI; ++i)
+  for (int i = 0; i < NI; ++i) {
+    const int v = tid + 256 * i;
+    inside[i] = (NVEC % 256 == 0 || v < NVEC) && v < row_vecs;
 #pragma unroll
     for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
+  }
 #pragma unroll 2
   for (int k = b0; k < b1; ++k) {  // group sum, in batch order
     const T* src = base + (int64_t)grp_batches[k] * a.ldg;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int v = tid + 256 * i;
-      if (NVEC % 256 == 0 || v < NVEC) load_add<NT>(src + v * LV, acc[i]);
-    }
+    for (int i = 0; i < NI; ++i)
+      if (inside[i]) load_add<NT>(src + (tid + 256 * i) * LV, acc[i]);
   }
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
@@ -413,6 +417,7 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t ti
 #pragma unroll
   for (int l = 0; l < M; ++l) y[l] = ybar[tid * M + l];
   float* zbase = a.Z + tile * 256 + tid;
+  if (tile * 256 + tid >= a.d_c) return;  // partial last tile
   for (int t = n0; t < n1; ++t) {
     const int j = grp_nodes[t];
     const float wj = w[j];
@@ -517,6 +522,13 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         if (phase_grid > 0) {
           // a last position that only a few blocks would work on (the others idle through it) goes to the flat kernel
           if (ptiles >= phase_grid && (ptiles % phase_grid) * 8 < ptiles) phase_tiles = ptiles - ptiles % phase_grid;
+          // a last position that is less than 60 % filled: the same number of positions on a smaller grid, every block busy in
+          // each (measured at P = 100 on 7.3 M parameters: 716 block-tiles on 358 blocks 6.08 TB/s, on 512 blocks 5.81;
+          // a last position 89 % filled is better left alone: 969 tiles on 512 blocks 6.58 TB/s, on 485 blocks 6.38)
+          if (grid_cap <= 0 && phase_tiles % phase_grid != 0 && (phase_tiles % phase_grid) * 10 < (int64_t)phase_grid * 6) {
+            const int64_t positions = (phase_tiles + phase_grid - 1) / phase_grid;
+            phase_grid = (int)((phase_tiles + positions - 1) / positions);
+          }
           const int64_t n32 = (phase_tiles + (int64_t)phase_grid * UT32 - 1) / ((int64_t)phase_grid * UT32);
           const int64_t n40 = (phase_tiles + (int64_t)phase_grid * UT40 - 1) / ((int64_t)phase_grid * UT40);
           wide = UT40 > UT32 && n40 < n32;
@@ -541,13 +553,14 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         done_chunks = phase_tiles * 1024;
       }
       const int64_t tile0 = phase_grid > 0 ? 4 * phase_tiles : 0;  // flat tiles of 256 chunks from here on
-      const int64_t ntiles = plan->d / (256 * M) - tile0;
+      // a row that ends on a vector boundary: its partial last tile goes along (no separate launch for the ragged tail)
+      const int64_t ntiles = (plan->d % LV == 0 ? (plan->d + 256 * M - 1) / (256 * M) : plan->d / (256 * M)) - tile0;
       if (ntiles > 0) {
         dim3 grid((unsigned)ntiles, (unsigned)q);
         if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
         else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
-        done_chunks = (tile0 + ntiles) * 256;
+        done_chunks = std::min<int64_t>((tile0 + ntiles) * 256, plan->d_c);
       }
     }
   }

@@ -121,6 +121,7 @@ SMALL = [
     (7, 1, 1, 4096), (7, 1, 1, 70_001), (15, 1, 2, 40_002), (15, 1, 2, 131_073), (31, 2, 2, 50_000),
     (63, 3, 4, 40_004), (63, 3, 4, 65_539), (100, 5, 4, 33_001), (9, 1, 3, 30_001), (20, 2, 5, 25_003),
     (100, 5, 10, 50_010), (24, 2, 8, 64_001), (4, 1, 2, 2), (4, 1, 2, 1), (10, 3, 4, 3), (26, 1, 6, 40_003), (30, 2, 7, 30_007),
+    (100, 5, 10, 50_020), (20, 2, 5, 25_020), (30, 2, 7, 30_016), (12, 1, 6, 1_000),   # rows that end on a vector boundary inside a tile
 ]
 
 
@@ -158,6 +159,19 @@ def test_all_adversaries_in_one_group_and_fewer_than_s(P, s, m):
     run_case(P, s, m, 16_384, attack="mix", byz=oplan.nodes[oplan.q - 1][-s:].tolist(), seed=2)
     run_case(P, s, m, 16_384, attack="noise100", n_byz=s - 1, seed=3)
     run_case(P, s, m, 16_384, attack="noise100", n_byz=0, seed=4)
+
+
+def test_more_than_eight_adversaries_per_group():
+    """Locator degrees above eight leave the one-set-per-lane path: the system is solved by Householder QR in LDS and
+    the candidate sets go through the whole wavefront one at a time.  Groups of 22 to 26 nodes; brute force is out of
+    reach here (more than 2e5 subsets), the references are the oracle's phi and the planted set."""
+    oplan = so.make_plan(44, 10, 2)
+    run_case(22, 10, 2, 9_000, attack="mix", n_byz=10, seed=61)
+    run_case(22, 10, 2, 9_000, attack="noise100", n_byz=4, seed=62)
+    run_case(22, 10, 2, 9_000, attack="flip10", n_byz=0, seed=63)
+    run_case(44, 10, 2, 12_002, attack="mix", byz=oplan.nodes[1][:10].tolist(), seed=64)      # all ten in the second group
+    run_case(26, 9, 8, 32_008, attack="paper", n_byz=9, seed=65)
+    run_case(22, 10, 2, 6_000, attack="huge", n_byz=3, seed=66)
 
 
 def test_unaligned_rows_use_general_kernels():
@@ -448,7 +462,8 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
 
 
 @pytest.mark.parametrize("P,s,m,d,phase", [(63, 3, 4, 131_075, 1), (63, 3, 4, 40_004, 0), (15, 1, 2, 40_002, 1), (7, 1, 1, 70_001, 1),
-                                          (100, 5, 10, 50_010, 0), (20, 2, 5, 25_003, 0), (100, 5, 4, 33_001, 0)])
+                                          (100, 5, 10, 50_010, 0), (20, 2, 5, 25_003, 0), (100, 5, 4, 33_001, 0), (100, 5, 10, 50_020, 0),
+                                          (30, 2, 7, 30_016, 0)])
 def test_decode_fused_with_the_sgd_step(P, s, m, d, phase):
     """solon_decode_update against the oracle's decode followed by w <- w - step * u (Sec. 3.1), through every
     recombination kernel (flat, tiled, phase-separated): each parameter within one fp32 rounding of its own size plus
