@@ -125,6 +125,8 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
     else:
         enc_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
         loc_ms, dec_ms = ms_step - enc_ms, 0.0               # everything of a step that is not the encoder: the one-pass call (and the gaps)
+    enc_all = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    enc_stats = dict(mean=enc_ms, median=enc_all[len(enc_all) // 2], min=enc_all[0], max=enc_all[-1])
     ab = algorithmic_bytes(cfg, plan)
     if not two_pass:                                         # for the record: the two separate passes, a few steps
         ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(max(3, steps // 4))]
@@ -145,7 +147,7 @@ def run_config(name, steps, warmup, want_cpu_baseline, cfg=None, check_sum=False
                             else "locate_decode (fell back to two passes: m not in {1, 2, 4} or input too small)"),
         bytes_moved=mb, GBps_moved=mb["total"] / (ms_step * 1e-3) / 1e9,
         pct_of_peak_moved=100.0 * mb["total"] / (ms_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        fresh_f_per_step=len(fs), recombination_repeated_in_last_step=bool(redone),
+        fresh_f_per_step=len(fs), recombination_repeated_in_last_step=bool(redone), encode_ms_over_steps=enc_stats,
     )
     if two_pass:
         res["phase_ms"] = dict(encode=enc_ms, locate=loc_ms, decode=dec_ms)
@@ -484,6 +486,7 @@ def main():
         "phase_ms": main_res["phase_ms"], "phase_GBps": main_res["phase_GBps"], "phase_GBps_moved": main_res["phase_GBps_moved"],
         "two_pass_phase_ms": main_res.get("two_pass_phase_ms"), "two_pass": main_res.get("two_pass"),
         "redo_path_ms": main_res.get("redo_path_ms"), "fresh_f_per_step": main_res["fresh_f_per_step"],
+        "encode_ms_over_steps": main_res["encode_ms_over_steps"],
         "located_ok": main_res["located_ok"],
         "roofline": {"kernel": "encode_phase_kernel (solon_encode; the persistent phase-separated encoder serves this size)", "bound": "hbm", "achieved": enc_bytes / enc_s / 1e9,
                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": enc_bytes / enc_s / 1e9 / PEAK_HBM_GBS, "traffic": traffic,
