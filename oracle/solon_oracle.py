@@ -272,6 +272,41 @@ def _locate_group_bruteforce_stacked(wg, rho_g, s, m, tau):
     return None
 
 
+def _group_explanations(wg, rho_g, s, m, tau):
+    """ALL subsets of the smallest size that explain the group (same fits and test as the enumeration above, stacked).
+    Over the reals there is exactly one (Lemma 1); at a finite threshold a deviation that the fit can absorb by bending
+    towards a neighbouring point - end points of a long group at large m - may leave two.  Tests use this to tell a
+    unique located set from an ambiguous one."""
+    n = len(wg)
+    nonfinite = [i for i in range(n) if not np.isfinite(rho_g[i])]
+    sc = _scale(rho_g)
+    if sc == 0.0:
+        return [nonfinite] if len(nonfinite) <= s else []
+    y = np.where(np.isfinite(rho_g), rho_g / sc, 0.0)
+    A = _cheb.chebvander(wg, m - 1)
+    for e in range(len(nonfinite), s + 1):
+        subsets = [S for S in combinations(range(n), e) if all(i in S for i in nonfinite)]
+        if not subsets:
+            continue
+        keep = np.ones((len(subsets), n))
+        if e:
+            keep[np.arange(len(subsets))[:, None], np.array(subsets)] = 0.0
+        Qm, Rm = np.linalg.qr(A[None, :, :] * keep[:, :, None])
+        coef = np.linalg.solve(Rm, (Qm.transpose(0, 2, 1) @ (y[None, :] * keep)[:, :, None]))[:, :, 0]
+        res = np.abs(coef @ A.T - y[None, :])
+        ok = np.all((res <= tau) | (keep == 0.0), axis=1)
+        if ok.any():
+            return [sorted(subsets[i]) for i in np.flatnonzero(ok)]
+    return []
+
+
+def explanations(plan, rho, g, tau=TAU):
+    """Every smallest set of nodes of group g (global indices) without which the group's projections are consistent."""
+    idx = plan.nodes[g]
+    sets = _group_explanations(plan.w[idx].astype(np.float64), np.asarray(rho, dtype=np.float64)[idx], plan.s, plan.m, tau)
+    return [[int(idx[i]) for i in S] for S in sets]
+
+
 def _locator_system(wg, y, m, s):
     """[W_{m+s-1}, -W_{s-1} .* (y 1^T)] a = y .* T_s(w): the system of Sec. 3.4 written in the
     Chebyshev basis (a change of basis of the unknown polynomials; the locator's leading

@@ -56,3 +56,22 @@ def one_group_round(base, attack, P, s, m, d, n, n_byz):
     """(plan, rho, planted set) of the same round, projected by the oracle."""
     plan, R, f, byz = one_group_inputs(base, attack, P, s, m, d, n, n_byz)
     return plan, so.project(R, f), byz
+
+
+def mixed_strength_projections(P, s, m, deltas, seed):
+    """Projections of one group whose s corrupted nodes differ widely in strength: node t is scaled by -100 ("big") or has
+    noise of deltas[t] times its message's mean magnitude added - the recipe under which weakly corrupted nodes come late
+    in the order of the locator's roots.  Returns (plan, rho, planted set, smallest planted deviation in units of tau)."""
+    rng = np.random.default_rng(seed)
+    plan = so.make_plan(P, s, m)
+    G = (rng.standard_normal((P, 512 * m)) * 0.01).astype(np.float32)
+    Z = so.encode(plan, G).astype(np.float32).astype(np.float64)
+    byz = sorted(rng.choice(P, size=s, replace=False).tolist())
+    R = Z.copy()
+    for t, j in enumerate(byz):
+        dl = deltas[t % len(deltas)]
+        R[j] = -100.0 * Z[j] if dl == "big" else Z[j] + dl * np.abs(Z[j]).mean() * rng.standard_normal(Z.shape[1])
+    f = (1 + rng.standard_normal(Z.shape[1])).astype(np.float32)
+    rho = so.project(R, f).astype(np.float32).astype(np.float64)       # what the HIP path is handed below, exactly
+    dev = np.abs(so.project(R - Z, f)) / so._scale(rho)
+    return plan, rho, byz, float(min(dev[j] for j in byz)) / so.TAU

@@ -11,7 +11,7 @@ above and all rounding far below either value.
 import numpy as np
 import pytest
 
-from locator_rounds import GROUP_SHAPES, RECIPES, one_group_round
+from locator_rounds import GROUP_SHAPES, RECIPES, mixed_strength_projections, one_group_round
 from oracle import solon_oracle as so
 
 
@@ -121,3 +121,26 @@ def test_search_gives_up_only_when_no_small_set_explains_the_group():
     for n in range(6):
         plan, rho, _ = one_group_round("X1", "paper", 11, 3, 4, 1024, n, 4)
         assert located(plan, rho, "bw") == located(plan, rho, "bruteforce") == "error %d" % so.E_DECODE
+
+
+def test_explanations_are_the_bruteforce_answer_alone_on_clear_rounds():
+    """With every planted deviation thousands of tau, exactly one smallest set explains a group: the one brute force
+    returns, the planted one (Lemma 1)."""
+    for n in range(24):
+        base, attack = RECIPES[n % len(RECIPES)]
+        plan, rho, byz = one_group_round(base, attack, 14, 5, 4, 1024, n, n % 6)
+        assert so.explanations(plan, rho, 0) == [located(plan, rho, "bruteforce")] == [byz]
+
+
+def test_a_finite_threshold_can_leave_two_explanations():
+    """(20, 5, 10), one node scaled by -100 and four with noise of a tenth of their message's size; node 19 - an end
+    point - deviates by 174 tau.  Leaving out its neighbour 18 instead lets the fit bend through the corrupted value and
+    still passes within 0.82 tau: two smallest explanations, of which the enumeration in lexicographic order (brute
+    force) returns the one that is NOT planted.  The located set is only as unique as the threshold allows; tests that
+    demand the planted set plant deviations of at least 1000 tau and check that the explanation is unique."""
+    plan, rho, byz, margin = mixed_strength_projections(20, 5, 10, ["big", 1e-1, 1e-1, 1e-1, 1e-1], 49)
+    valid = so.explanations(plan, rho, 0)
+    assert byz == [9, 14, 15, 16, 19] and 100 < margin < 1000
+    assert byz in valid and [9, 14, 15, 16, 18] in valid and len(valid) == 2
+    assert located(plan, rho, "bruteforce") == [9, 14, 15, 16, 18]
+    assert located(plan, rho, "bw") in valid
