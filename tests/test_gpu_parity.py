@@ -377,20 +377,29 @@ def test_the_guess_sample_cannot_be_avoided_through_a_fixed_window():
         solon.solon_tune("fuse_sample_leading", 0)
 
 
-def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
-    cfg = dict(P=63, d=2_000_000, dtype="f32", dist="normal", sigma=0.01)
-    plan = solon.Plan(63, 3, 4, cfg["d"])
-    G = workloads.make_gradients(cfg, DEV, 61, d=cfg["d"])
-    Z = torch.zeros((63, plan.d_c), dtype=torch.float32, device=DEV)
+@pytest.mark.parametrize("path,P,s,m,d", [("one_pass", 63, 3, 4, 2_000_000), ("one_pass", 42, 2, 2, 1_600_000), ("two_passes", 100, 5, 10, 1_000_010),
+                                          ("two_passes", 31, 2, 3, 600_001)])
+def test_locate_decode_equals_two_passes_bitwise_and_reports_failure(path, P, s, m, d):
+    """solon_locate_decode against solon_locate + solon_decode: same V, same projections, the same bits in u - through the
+    one-pass kernel, whether the guess holds (corruption visible in the sample), fails (invisible: recombination repeated)
+    or there is nothing to find, and through the two passes it takes for other m and for plans with idle nodes; a group
+    with more than s corrupted nodes is reported as by solon_locate."""
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    plan = solon.Plan(P, s, m, d)
+    oplan = so.make_plan(P, s, m)
+    G = workloads.make_gradients(cfg, DEV, 61, d=d)
+    Z = torch.zeros((P, plan.d_c), dtype=torch.float32, device=DEV)
     solon.solon_encode(plan, G, Z)
     f = workloads.make_projection(plan.d_c, DEV, 62)
-    ua = torch.zeros(cfg["d"], dtype=torch.float32, device=DEV)
+    ua = torch.zeros(d, dtype=torch.float32, device=DEV)
     ub = torch.zeros_like(ua)
+    g0 = oplan.nodes[0].tolist()
+    spread = sorted(int(oplan.nodes[g][k]) for g, k in zip(range(min(s, oplan.q)), (1, 0, 2, 0, 1)))
     try:
         solon.solon_tune("fuse", 1)
         solon.solon_tune("fuse_sample", 1024)
         solon.solon_tune("fuse_sample_leading", 1)
-        for byz, from_col in (([], 0), ([3, 40, 62], 0), ([3, 40, 62], 2048), ([0, 1, 2], 5000)):
+        for byz, from_col, redo in (([], 0, 0), (spread, 0, 0), (spread, 2048, None), (g0[:s], 5000, 1)):   # a group's first node is always guessed
             R = workloads.apply_attack(Z.clone(), byz, "mix", 63)
             if from_col:
                 R[:, :from_col] = Z[:, :from_col]
@@ -400,11 +409,14 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
                 ub.zero_()
                 Vb, rho_b = solon.solon_locate_decode(plan, R, f, ub, want_rho=True)
                 torch.cuda.synchronize()
+                assert plan.query(solon.SOLON_Q_LAST_ONE_PASS) == (1 if path == "one_pass" else 0)
+                if path == "one_pass":
+                    assert redo is None or plan.query(solon.SOLON_Q_LAST_REDO) == redo, (byz, from_col)
                 assert Va == Vb == sorted(byz)
                 assert np.allclose(rho_a, rho_b, rtol=1e-12, atol=0)
                 assert torch.equal(ua, ub), (byz, from_col)
         # more than s corrupted nodes in one group: reported, as by solon_locate
-        R = workloads.apply_attack(Z.clone(), [0, 1, 2, 3], "noise100", 64)
+        R = workloads.apply_attack(Z.clone(), g0[:s + 1], "noise100", 64)
         with pytest.raises(solon.SolonError) as e:
             solon.solon_locate_decode(plan, R, f, ub)
         assert e.value.code == solon.SOLON_E_DECODE
@@ -414,25 +426,28 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure():
         solon.solon_tune("fuse_sample_leading", 0)
 
 
-def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+@pytest.mark.parametrize("path", ["one_pass", "two_passes"])
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(path):
     """The asynchronous calls allocate nothing, clear nothing with memsets and never wait for the host, so a whole step
     (encode, then phi and psi) can be recorded once into a HIP graph; every replay - with eager work in between - gives
     the eager result.  The persistent kernels are forced, so their self-resetting arrival counters go through replays."""
-    cfg = dict(P=63, d=1_200_004, dtype="f32", dist="normal", sigma=0.01)
+    cfg = dict(P=63, d=1_200_000 if path == "one_pass" else 1_200_004, dtype="f32", dist="normal", sigma=0.01)   # the one-pass kernel needs aligned rows
     plan = solon.Plan(63, 3, 4, cfg["d"])
     G = workloads.make_gradients(cfg, DEV, 71, d=cfg["d"])
     Z = torch.zeros((63, plan.d_c), dtype=torch.float32, device=DEV)
     u = torch.zeros(cfg["d"], dtype=torch.float32, device=DEV)
     f = workloads.make_projection(plan.d_c, DEV, 72)
     byz = [5, 30, 61]
-    for knob in ("encode_phase", "decode_phase", "fuse"):
+    for knob in ("encode_phase", "decode_phase"):
         solon.solon_tune(knob, 1)
+    solon.solon_tune("fuse", 1 if path == "one_pass" else 0)
     solon.solon_tune("fuse_sample", 4096)
     try:
         solon.solon_encode(plan, G, Z)
         R = workloads.apply_attack(Z.clone(), byz, "mix", 73)
         V, _ = solon.solon_locate_decode(plan, R, f, u)                       # eager reference (and warm-up)
         assert V == byz
+        assert plan.query(solon.SOLON_Q_LAST_ONE_PASS) == dict(one_pass=1, two_passes=0)[path]
         Z_ref, u_ref = Z.clone(), u.clone()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
