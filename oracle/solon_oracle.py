@@ -38,7 +38,8 @@ sums; linearity; message length of Table 2; bound tightness construction of Thm.
 Parity unpinned by the paper: the numerical thresholds (TAU, the median scale, the rank tolerance).
 The paper works over the reals ("!=", "with probability equal to unity"); these values are this
 build's reading and are pinned only by requiring brute force, locate_bw, the HIP path and the planted
-truth to coincide on every test and bench input.
+truth to coincide on every test and bench input, and - for TAU - by a window: at 1e-2 a corruption gets
+through that costs the decoded sum more than 1e-4, at 1e-8 fp32 rounding of honest messages is reported.
 """
 from itertools import combinations
 

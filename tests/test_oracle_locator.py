@@ -5,8 +5,10 @@ decodes, whatever the strengths of the corruptions; these sweeps hold phi to tha
 paper's own group shapes and recipes.  Brute force is the reference; phi is the method under test.
 
 Thresholds that the paper does not fix (tau = 1e-4 of the median |rho|, the rank cut-off of the least-squares
-solve) stay unpinned by it: changing tau to 1e-2 passes every test here, since all planted corruptions are far
-above and all rounding far below either value.
+solve) stay unpinned by it.  The tests at the end of this file bound tau from both sides by what the path must
+deliver - two decades up (1e-2) a corruption slips through that costs the decoded sum more than the 1e-4 it is held
+to, four decades down (1e-8) honest fp32 rounding is reported as corruption in every round - but no test fixes the
+value inside that window: all planted corruptions of the other tests are far above it and all rounding far below.
 """
 import numpy as np
 import pytest
@@ -144,3 +146,50 @@ def test_a_finite_threshold_can_leave_two_explanations():
     assert byz in valid and [9, 14, 15, 16, 18] in valid and len(valid) == 2
     assert located(plan, rho, "bruteforce") == [9, 14, 15, 16, 18]
     assert located(plan, rho, "bw") in valid
+
+
+def _one_noisy_node(P, s, m, delta, seed):
+    """One group; the node psi would pick first (largest |w|) adds noise of `delta` times its message's mean magnitude."""
+    rng = np.random.default_rng(seed)
+    plan = so.make_plan(P, s, m)
+    d = 256 * m
+    G = (rng.standard_normal((P, d)) * 0.01).astype(np.float32)
+    Z = so.encode(plan, G).astype(np.float32).astype(np.float64)
+    j = int(plan.nodes[0][int(np.argmax(np.abs(plan.w[plan.nodes[0]])))])
+    R = Z.copy()
+    if delta:
+        R[j] += delta * np.abs(Z[j]).mean() * rng.standard_normal(Z.shape[1])
+    f = (1 + rng.standard_normal(Z.shape[1])).astype(np.float32)
+    return plan, G, R, so.project(R, f), j
+
+
+def test_a_threshold_two_decades_larger_lets_harmful_corruption_through():
+    """Upper bound on tau from the bar on u.  A node that adds noise of 3e-3 of its message (about 30 tau in the
+    projection) is located at tau = 1e-4 and the sum comes back to rounding; at tau = 1e-2 it passes as honest, psi uses
+    its row, and the decoded sum is off by more than the 1e-4 the path is held to (Def. 1: the exact sum)."""
+    missed = 0
+    for seed in range(10):
+        plan, G, R, rho, j = _one_noisy_node(15, 1, 2, 3e-3, seed)
+        u_true = G.astype(np.float64).sum(axis=0)
+        V = so.locate(plan, rho, "bw")
+        assert V == [j] == so.locate(plan, rho, "bruteforce_stacked")
+        assert so.rel_l2(so.decode(plan, R, V, G.shape[1]), u_true) < 1e-6
+        V_loose = so.locate(plan, rho, "bw", tau=1e-2)
+        if V_loose == []:
+            missed += 1
+            assert so.rel_l2(so.decode(plan, R, V_loose, G.shape[1]), u_true) > 1e-4
+    assert missed >= 8
+
+
+@pytest.mark.parametrize("P,s,m", [(15, 1, 2), (14, 5, 4), (20, 5, 10)])
+def test_a_threshold_four_decades_smaller_reports_honest_rounding(P, s, m):
+    """Lower bound on tau from the fp32 wire.  With nobody corrupted, messages rounded to fp32 leave residuals of
+    1e-8 ... 1e-6 of the median projection: tau = 1e-4 reports nobody in any round, tau = 1e-8 reports honest nodes (or gives
+    the group up) in every round."""
+    for seed in range(10):
+        plan, G, R, rho, j = _one_noisy_node(P, s, m, 0.0, seed)
+        assert so.locate(plan, rho, "bw") == []
+        try:
+            assert so.locate(plan, rho, "bw", tau=1e-8) != []
+        except so.OracleError as e:
+            assert e.code == so.E_DECODE
