@@ -178,7 +178,7 @@ int solon_decode_update(solon_plan* plan, const float* R, int64_t ldr, const int
  * repeated with the right rows, decided on the device.  When a group's status is not SOLON_OK, u is unspecified.
  * Reads R about once instead of
  * 1 + q m / P times.  Falls back to the two separate passes for m other than 1, 2, 4, unaligned buffers, plans with
- * idle nodes and small inputs.
+ * idle nodes and inputs on which the saved second read of q m rows does not pay for the guess (rows of R below roughly 1.5 GB in all).
  *   R, f            device, as for solon_locate
  *   u               device, d fp32, as for solon_decode
  *   byz_idx, n_byz, rho_out   host or NULL, as for solon_locate; asynchronous when all three are NULL

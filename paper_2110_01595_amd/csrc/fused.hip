@@ -194,7 +194,16 @@ static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const
   if ((int64_t)grid * FUSE_BLOCK * 16 >= ((int64_t)1 << 32)) return 0;  // 32-bit lane offsets inside a round
   const int64_t per_pass = (int64_t)grid * FUSE_BLOCK;  // units of a round
   const int64_t npass = (nunits + per_pass - 1) / per_pass;
-  if (want < 0 && npass < 8) return 0;  // measured: on small inputs the two separate passes are faster
+  if (want < 0) {
+    // Does one pass pay?  It saves the second read of the q m rows psi uses (a share q m / P of R) and costs the guess (sample
+    // projection, sum, solve: about 200 MB worth of streaming time) plus the idle part of a last, partly filled round of the
+    // persistent grid.  Fitted on P = 15 ... 100, m = 1, 2 and 4, rows of 1.8 M ... 45 M columns: the choice is the faster one at all 25
+    // points measured (the pass is 4 - 18 % faster wherever this is positive, 1 - 14 % slower where it is negative).
+    const double share = (double)plan->q * plan->m / plan->P;
+    const double fill = (double)nunits / ((double)npass * (double)per_pass);
+    const double gain = share - 0.5 * (1.0 / fill - 1.0) - 2.0e8 / ((double)plan->P * (double)plan->d_c * 4.0);
+    if (gain < 0.02) return 0;
+  }
   if (npass * grid + 64 > SOLON_PROJ_MAX_TILES) return 0;
   *per_pass_out = per_pass;
   return grid;
