@@ -359,6 +359,73 @@ def sweep_conditioning():
             print(json.dumps(out), flush=True)
 
 
+def sweep_two_streams(steps, warmup):
+    """Two independent rounds (two jobs served by the same GPU: own plan, gradients, messages, f, u) issued on ONE stream one
+    after the other, and on TWO streams side by side.  Every phase is bound by the same HBM, so the streams can only fill each
+    other's gaps: launch latencies, the latency-bound solves, ramp-up and drain of every kernel."""
+    import torch
+
+    import paper_2110_01595_amd as solon
+    import workloads
+
+    dev = torch.device("cuda:0")
+    shapes = [(n, workloads.CONFIGS[n], workloads.seeds(n)) for n in ("C5", "C4", "C3", "C2", "X1")]
+    shapes.append(("LSTM_P100_s5_m10", dict(P=100, s=5, m=10, d=7_332_000, dtype="f32", dist="normal", sigma=0.01, attack="paper"), dict(G=1, f=2, byz=3, attack=4)))
+    for name, cfg, sd in shapes:
+        P, s, m, d = cfg["P"], cfg["s"], cfg["m"], cfg["d"]
+        jobs = []
+        for j in range(2):
+            plan = solon.Plan(P, s, m, d, dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
+            d_c = plan.d_c
+            G = workloads.make_gradients(cfg, dev, sd["G"] + 50 * j)
+            ld = (d_c + 63) // 64 * 64
+            Z = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
+            R = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
+            u = torch.empty(d, dtype=torch.float32, device=dev)
+            f = workloads.make_projection(d_c, dev, sd["f"] + 50 * j)
+            byz = workloads.pick_byzantine(P, s, sd["byz"] + 50 * j)
+            solon.solon_encode(plan, G, Z)
+            R.copy_(Z)
+            workloads.apply_attack(R, byz, cfg["attack"], sd["attack"] + 50 * j)
+            jobs.append(dict(plan=plan, G=G, Z=Z, R=R, u=u, f=f, byz=byz))
+        torch.cuda.synchronize()
+
+        def round_(job):
+            solon.solon_encode(job["plan"], job["G"], job["Z"])
+            solon.solon_locate_decode(job["plan"], job["R"], job["f"], job["u"], want_host=False)
+
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        ms = {}
+        ref = None
+        for mode in ("one_stream", "two_streams"):
+            def both():
+                for j, job in enumerate(jobs):
+                    if mode == "two_streams":
+                        with torch.cuda.stream(streams[j]):
+                            round_(job)
+                    else:
+                        round_(job)
+            for _ in range(warmup):
+                both()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                both()
+            torch.cuda.synchronize()
+            ms[mode] = (time.perf_counter() - t0) * 1e3 / steps / 2          # per round
+            ok = all(solon.solon_decode_status(job["plan"]) == 0 for job in jobs)
+            got = [job["u"].clone() for job in jobs]
+            if ref is None:
+                ref = got
+            same = all(torch.equal(a, b) for a, b in zip(ref, got))
+        ab = algorithmic_bytes(cfg, jobs[0]["plan"])
+        print(json.dumps(dict(workload=name, ms_per_round=ms, speedup=ms["one_stream"] / ms["two_streams"],
+                              pct_of_peak={k: ab["total"] / (v * 1e-3) / 1e9 / PEAK_HBM_GBS * 100 for k, v in ms.items()},
+                              status_ok=ok, same_u_both_ways=same)), flush=True)
+        del jobs
+        torch.cuda.empty_cache()
+
+
 def sweep_repetition(steps, warmup):
     """m = 1 (repetition code): the general locate + decode path next to the majority-vote decoder, same inputs."""
     import torch
@@ -423,10 +490,11 @@ def main():
     ap.add_argument("--two-pass", action="store_true", help="time solon_locate + solon_decode instead of solon_locate_decode")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
                     help="launch-shape knob passed to solon_tune before the run (measurement aid; may be repeated)")
-    ap.add_argument("--sweep", choices=["paper", "repetition", "conditioning"], default=None,
+    ap.add_argument("--sweep", choices=["paper", "repetition", "conditioning", "two_streams"], default=None,
                     help="instead of the headline line: 'paper' runs the paper's cost-study shapes, 'repetition' compares the "
                          "m = 1 majority-vote decoder with the general path, 'conditioning' takes the compression ratio up to "
-                         "16 and records where located set and decode error leave the bar; one JSON line per shape")
+                         "16 and records where located set and decode error leave the bar, 'two_streams' times two independent rounds on one "
+                         "stream and on two; one JSON line per shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain device copy of 4 GiB (reads 4 GiB, writes 4 GiB): the dispatch whose rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels")
@@ -458,6 +526,9 @@ def main():
         return
     if args.sweep == "conditioning":
         sweep_conditioning()
+        return
+    if args.sweep == "two_streams":
+        sweep_two_streams(args.steps, args.warmup)
         return
 
     main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline, two_pass=args.two_pass)

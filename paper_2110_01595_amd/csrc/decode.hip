@@ -212,7 +212,7 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
     }
     if (phase_grid > 0) {
       hipLaunchKernelGGL((recombine_phase_kernel<M>), dim3((unsigned)phase_grid), dim3(1024), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
-                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), run_flag, step, update);
+                         plan->dev.dec_coef, u, punits, plan->dev.grid_sync, solon_tuning("phase_spin_limit", SOLON_SPIN_LIMIT), run_flag, step, update);
       SOLON_HIP(hipGetLastError());
       p_begin = punits * PCH;  // a multiple of every CH used below
     }

@@ -489,7 +489,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       if (phase_grid > 0) {
         const uint32_t pace8 = solon_store_pace8((int64_t)phase_grid * 1024 * (LV / M) * (int64_t)sizeof(float));
         hipLaunchKernelGGL((encode_phase_kernel<M, T>), dim3((unsigned)phase_grid), dim3(1024), 0, st, a, nunits, q, plan->dev.grid_sync,
-                           solon_tuning("phase_spin_limit", 400), pace8, ENC_TABLE_ARGS(a));
+                           solon_tuning("phase_spin_limit", SOLON_SPIN_LIMIT), pace8, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = nunits * (LV / M);
       } else if (nunits > 0) {
@@ -545,10 +545,10 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       if (phase_grid > 0) {
         if (wide)
           hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 40>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, phase_tiles, q,
-                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
+                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", SOLON_SPIN_LIMIT), ENC_TABLE_ARGS(a));
         else
           hipLaunchKernelGGL((encode_tile_phase_kernel<M, T, 32>), dim3((unsigned)phase_grid), dim3(1024), lds, st, a, phase_tiles, q,
-                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", 400), ENC_TABLE_ARGS(a));
+                             plan->dev.grid_sync, solon_tuning("phase_spin_limit", SOLON_SPIN_LIMIT), ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = phase_tiles * 1024;
       }

@@ -254,7 +254,7 @@ extern "C" int solon_locate_decode(solon_plan* plan, const float* R, int64_t ldr
     a.R = R; a.ldr = ldr; a.f = f; a.nunits = nunits; a.P = P; a.q = plan->q;
     a.grp_off = plan->dev.grp_off; a.order = plan->dev.spec_order; a.coef = plan->dev.spec_coef;
     a.partials = plan->dev.partials; a.u = u; a.sync = plan->dev.grid_sync;
-    a.spin_limit = solon_tuning("fuse_spin_limit", 400);
+    a.spin_limit = solon_tuning("fuse_spin_limit", SOLON_SPIN_LIMIT);
     rc = m == 1 ? fused_pass<1>(plan, a, grid, st) : m == 2 ? fused_pass<2>(plan, a, grid, st) : fused_pass<4>(plan, a, grid, st);
     if (rc != SOLON_OK) return rc;
     int tiles = (int)((nunits + per_pass - 1) / per_pass) * grid;

@@ -6,7 +6,7 @@
 // for some tens of microseconds (results parked in registers), then write, then read again, gets most of that
 // back.  The alignment below only shapes timing; no data passes between blocks, so it needs no memory ordering,
 // and every wait is bounded: a block that has waited `spin_limit` polls simply goes on (the result is the same,
-// only slower), so the grid drains even if its blocks are not all resident at once.
+// only slower) and tells the others not to wait either, so the grid drains even if its blocks are not all resident at once.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -15,10 +15,18 @@
 #define SOLON_SYNC_STRIDE 32      // words between counters: 128 bytes, one cache line each
 #define SOLON_SYNC_GLOBAL (SOLON_SYNC_GROUPS * SOLON_SYNC_STRIDE)
 #define SOLON_SYNC_EXIT (SOLON_SYNC_GLOBAL + SOLON_SYNC_STRIDE)
+// polls (a microsecond or two each) before a block gives up at an alignment point: healthy waits are the skew between the blocks of
+// one phase, some ten polls; a launch that shares the chip with another stream's kernels should go adrift early (measured with two
+// rounds on two streams: 400 polls cost C3 25 % against one stream, 60 polls 8 %; one stream alone is the same at 60 ... 400)
+#define SOLON_SPIN_LIMIT 100
+#define SOLON_SYNC_ADRIFT (SOLON_SYNC_EXIT + SOLON_SYNC_STRIDE)  // set once a block has waited in vain: nobody waits any more in this launch
 
 // The nbar-th alignment point of this launch (nbar = 1, 2, ...; every block calls it the same number of times).
 // Two levels keep the single hot address short of traffic: a block bumps the counter of its group, every
 // arrival that completes a round of its group bumps the grid-wide counter, and one thread per block polls that with sleeps in between.
+// A block that has polled `spin_limit` times in vain sets the launch adrift: the grid is evidently not resident as a whole
+// (another kernel - a second stream's, say - holds part of the chip), so waiting at every further point would cost the full
+// bound each time; from then on no block of this launch waits at all and the kernel runs like an unaligned one.
 __device__ __forceinline__ void solon_phase_align(uint32_t* sync, uint32_t nbar, int spin_limit) {
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -28,9 +36,14 @@ __device__ __forceinline__ void solon_phase_align(uint32_t* sync, uint32_t nbar,
     if ((old + 1u) % mates == 0u) __hip_atomic_fetch_add(sync + SOLON_SYNC_GLOBAL, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t ngroups = gridDim.x < SOLON_SYNC_GROUPS ? gridDim.x : SOLON_SYNC_GROUPS;
     int n = 0;
-    while (__hip_atomic_load(sync + SOLON_SYNC_GLOBAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nbar * ngroups && n < spin_limit) {
+    bool adrift = __hip_atomic_load(sync + SOLON_SYNC_ADRIFT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+    while (!adrift && __hip_atomic_load(sync + SOLON_SYNC_GLOBAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nbar * ngroups) {
+      if (++n > spin_limit) {
+        __hip_atomic_store(sync + SOLON_SYNC_ADRIFT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
       __builtin_amdgcn_s_sleep(16);
-      ++n;
+      adrift = __hip_atomic_load(sync + SOLON_SYNC_ADRIFT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
     }
   }
   __syncthreads();
@@ -63,6 +76,7 @@ __device__ __forceinline__ void solon_phase_exit(uint32_t* sync) {
       for (int x = 0; x < SOLON_SYNC_GROUPS; ++x)
         __hip_atomic_store(sync + SOLON_SYNC_STRIDE * x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(sync + SOLON_SYNC_GLOBAL, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(sync + SOLON_SYNC_ADRIFT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(sync + SOLON_SYNC_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }

@@ -247,7 +247,7 @@ extern "C" int solon_decode_majority(solon_plan* plan, const float* R, int64_t l
     if (rows_grid > 0)
       hipLaunchKernelGGL(majority_rows_kernel<9>, dim3((unsigned)rows_grid), dim3(1024), rlds, st, R, ldr, plan->q, plan->P, plan->dev.grp_off,
                          plan->dev.grp_nodes, u, units, plan->dev.vmask, plan->dev.status, plan->dev.grid_sync,
-                         solon_tuning("phase_spin_limit", 400));
+                         solon_tuning("phase_spin_limit", SOLON_SPIN_LIMIT));
     else if (plan->max_group <= 16)  // (an 8-node instance compiled to 234 registers per lane and ran slower than this one)
       hipLaunchKernelGGL(majority_reg_kernel<16>, grid, dim3(256), 0, st, R, ldr, plan->q, plan->dev.grp_off, plan->dev.grp_nodes, u,
                          plan->d, plan->dev.vmask, plan->dev.status);

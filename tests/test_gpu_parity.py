@@ -476,6 +476,61 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed(path):
         solon.solon_tune("fuse_sample", 1 << 17)
 
 
+def test_two_rounds_side_by_side_on_two_streams():
+    """Two plans working on two streams at once, with the persistent phase-separated kernels forced: each of their grids
+    wants the whole chip, so neither is resident as a whole, their alignment points cannot be met, and the launches go
+    adrift (every wait is bounded, then nobody waits any more).  That only changes timing: Z, V, status and u are the bits
+    of the same rounds run one after the other, also when the bound is a single poll."""
+    shapes = [(63, 3, 4, 2_000_000), (100, 5, 10, 1_000_010)]
+    jobs = []
+    for k, (P, s, m, d) in enumerate(shapes):
+        cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+        plan = solon.Plan(P, s, m, d)
+        G = workloads.make_gradients(cfg, DEV, 171 + k, d=d)
+        Z = torch.zeros((P, plan.d_c), dtype=torch.float32, device=DEV)
+        solon.solon_encode(plan, G, Z)
+        byz = workloads.pick_byzantine(P, s, 173 + k)
+        R = workloads.apply_attack(Z.clone(), byz, "mix", 175 + k)
+        jobs.append(dict(plan=plan, G=G, Z=Z, R=R, byz=byz, f=workloads.make_projection(plan.d_c, DEV, 177 + k),
+                         u=torch.zeros(d, dtype=torch.float32, device=DEV)))
+
+    def round_(job):
+        solon.solon_encode(job["plan"], job["G"], job["Z"])
+        solon.solon_locate_decode(job["plan"], job["R"], job["f"], job["u"], want_host=False)
+
+    for knob in ("encode_phase", "decode_phase", "fuse"):
+        solon.solon_tune(knob, 1)
+    try:
+        for job in jobs:
+            round_(job)
+        torch.cuda.synchronize()
+        ref = [(job["Z"].clone(), job["u"].clone()) for job in jobs]
+        for job in jobs:
+            assert solon.solon_locate(job["plan"], job["R"], job["f"])[0] == job["byz"]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for limit in (100, 1):
+            solon.solon_tune("phase_spin_limit", limit)
+            solon.solon_tune("fuse_spin_limit", limit)
+            for rep in range(3):
+                for job in jobs:
+                    job["Z"].zero_()
+                    job["u"].zero_()
+                torch.cuda.synchronize()
+                for _ in range(2):                                          # two rounds each, interleaved launch by launch
+                    for st, job in zip(streams, jobs):
+                        with torch.cuda.stream(st):
+                            round_(job)
+                torch.cuda.synchronize()
+                for job, (Z_ref, u_ref) in zip(jobs, ref):
+                    assert solon.solon_decode_status(job["plan"]) == solon.SOLON_OK
+                    assert torch.equal(job["Z"], Z_ref) and torch.equal(job["u"], u_ref), (limit, rep)
+    finally:
+        for knob in ("encode_phase", "decode_phase", "fuse"):
+            solon.solon_tune(knob, -1)
+        solon.solon_tune("phase_spin_limit", 100)
+        solon.solon_tune("fuse_spin_limit", 100)
+
+
 @pytest.mark.parametrize("P,s,m,d,phase", [(63, 3, 4, 131_075, 1), (63, 3, 4, 40_004, 0), (15, 1, 2, 40_002, 1), (7, 1, 1, 70_001, 1),
                                           (100, 5, 10, 50_010, 0), (20, 2, 5, 25_003, 0), (100, 5, 4, 33_001, 0), (100, 5, 10, 50_020, 0),
                                           (30, 2, 7, 30_016, 0)])
