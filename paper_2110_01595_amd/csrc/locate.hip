@@ -151,10 +151,12 @@ static void project_launch(bool vec, bool xcd_map, int nbunch, int ntiles, hipSt
 int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
                               int64_t ncols, int tile_base, int* ntiles_out, hipStream_t st, int64_t sample_of) {
   const int P = plan->P;
-  // rows per bunch: the fewest bunches of at most 16 rows, of equal size where P allows.  With the XCD-aware block
-  // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing (measured at P = 100:
-  // 16 rows 6.75 TB/s, 20 rows 6.67, 25 rows 5.7 - the last leaves too few resident waves).
-  const int rb_max = std::max(1, std::min(SOLON_PROJ_ROWS, solon_tuning("project_rows", 16)));
+  // rows per bunch: the fewest bunches of at most 4 rows, of equal size where P allows.  With the XCD-aware block
+  // numbering the bunches of a tile share f through one L2, so more rows per bunch buy nothing, and fewer rows mean more,
+  // lighter blocks (measured, whole solon_locate call: P = 15, rows of 22 MB: 16 rows 70.5 us, 8 rows 68.2, 4 rows 66.0;
+  // P = 63, 11 MB: 127.8 / 121.4 / 118.6; P = 100, 124 MB: 2244 / 2227 / 2208; 2 or 3 rows are no better than 4;
+  // 25 rows leave too few resident waves: 5.7 against 6.75 TB/s).
+  const int rb_max = std::max(1, std::min(SOLON_PROJ_ROWS, solon_tuning("project_rows", 4)));
   const int nbunch0 = (P + rb_max - 1) / rb_max;
   const int rb = (P + nbunch0 - 1) / nbunch0;
   const int nbunch = (P + rb - 1) / rb;
