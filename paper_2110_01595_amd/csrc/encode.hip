@@ -522,10 +522,11 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         if (phase_grid > 0) {
           // a last position that only a few blocks would work on (the others idle through it) goes to the flat kernel
           if (ptiles >= phase_grid && (ptiles % phase_grid) * 8 < ptiles) phase_tiles = ptiles - ptiles % phase_grid;
-          // a last position that is less than 60 % filled: the same number of positions on a smaller grid, every block busy in
-          // each (measured at P = 100 on 7.3 M parameters: 716 block-tiles on 358 blocks 6.08 TB/s, on 512 blocks 5.81;
-          // a last position 89 % filled is better left alone: 969 tiles on 512 blocks 6.58 TB/s, on 485 blocks 6.38)
-          if (grid_cap <= 0 && phase_tiles % phase_grid != 0 && (phase_tiles % phase_grid) * 10 < (int64_t)phase_grid * 6) {
+          // a last position that is less than 80 % filled: the same number of positions on a smaller grid, every block busy in
+          // each (measured at P = 100: 716 block-tiles (last position 40 % filled) on 358 blocks 6.08 TB/s, on 512 blocks 5.81;
+          // 66 - 78 % filled: 2.5 - 3.5 % faster balanced; 84 % filled: the same; 89 % filled is better left alone: 969 tiles on
+          // 512 blocks 6.58 TB/s, on 485 blocks 6.38)
+          if (grid_cap <= 0 && phase_tiles % phase_grid != 0 && (phase_tiles % phase_grid) * 10 < (int64_t)phase_grid * 8) {
             const int64_t positions = (phase_tiles + phase_grid - 1) / phase_grid;
             phase_grid = (int)((phase_tiles + positions - 1) / positions);
           }

@@ -205,7 +205,13 @@ static int fused_grid(const solon_plan* plan, const float* R, int64_t ldr, const
     if (gain < 0.02) return 0;
   }
   if (npass * grid + 64 > SOLON_PROJ_MAX_TILES) return 0;
-  *per_pass_out = per_pass;
+  // a partly filled last round: the same number of rounds on a smaller grid, every block busy in each (measured: 1.5 - 4.5 % faster
+  // with grids of 84 - 95 % of the resident one, e.g. 0.341 -> 0.328 ms at P = 31, m = 2, 25.6 M parameters; slower below 80 %)
+  if (cap <= 0) {
+    const int64_t even = (nunits + npass * FUSE_BLOCK - 1) / (npass * FUSE_BLOCK);
+    if (even * 10 >= (int64_t)grid * 8 && even < grid) grid = (int)even;
+  }
+  *per_pass_out = (int64_t)grid * FUSE_BLOCK;
   return grid;
 }
 
