@@ -19,7 +19,7 @@
 // one phase, some ten polls; a launch that shares the chip with another stream's kernels should go adrift early (measured with two
 // rounds on two streams: 400 polls cost C3 25 % against one stream, 60 polls 8 %; one stream alone is the same at 60 ... 400)
 #define SOLON_SPIN_LIMIT 100
-#define SOLON_SYNC_ADRIFT (SOLON_SYNC_EXIT + SOLON_SYNC_STRIDE)  // set once a block has waited in vain: nobody waits any more in this launch
+#define SOLON_SYNC_ADRIFT_BIT 0x80000000u  // in the grid-wide counter: set once a block has waited in vain, nobody waits any more in this launch
 
 // The nbar-th alignment point of this launch (nbar = 1, 2, ...; every block calls it the same number of times).
 // Two levels keep the single hot address short of traffic: a block bumps the counter of its group, every
@@ -35,15 +35,16 @@ __device__ __forceinline__ void solon_phase_align(uint32_t* sync, uint32_t nbar,
     const uint32_t old = __hip_atomic_fetch_add(sync + SOLON_SYNC_STRIDE * x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((old + 1u) % mates == 0u) __hip_atomic_fetch_add(sync + SOLON_SYNC_GLOBAL, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     const uint32_t ngroups = gridDim.x < SOLON_SYNC_GROUPS ? gridDim.x : SOLON_SYNC_GROUPS;
+    // the adrift mark is the top bit of the grid-wide counter, so a poll stays one load
     int n = 0;
-    bool adrift = __hip_atomic_load(sync + SOLON_SYNC_ADRIFT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-    while (!adrift && __hip_atomic_load(sync + SOLON_SYNC_GLOBAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nbar * ngroups) {
+    uint32_t seen = __hip_atomic_load(sync + SOLON_SYNC_GLOBAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    while ((seen & SOLON_SYNC_ADRIFT_BIT) == 0u && seen < nbar * ngroups) {
       if (++n > spin_limit) {
-        __hip_atomic_store(sync + SOLON_SYNC_ADRIFT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_or(sync + SOLON_SYNC_GLOBAL, SOLON_SYNC_ADRIFT_BIT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
       }
       __builtin_amdgcn_s_sleep(16);
-      adrift = __hip_atomic_load(sync + SOLON_SYNC_ADRIFT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+      seen = __hip_atomic_load(sync + SOLON_SYNC_GLOBAL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();
@@ -76,7 +77,6 @@ __device__ __forceinline__ void solon_phase_exit(uint32_t* sync) {
       for (int x = 0; x < SOLON_SYNC_GROUPS; ++x)
         __hip_atomic_store(sync + SOLON_SYNC_STRIDE * x, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(sync + SOLON_SYNC_GLOBAL, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(sync + SOLON_SYNC_ADRIFT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __hip_atomic_store(sync + SOLON_SYNC_EXIT, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }

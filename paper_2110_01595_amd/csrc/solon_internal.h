@@ -15,7 +15,7 @@
 // (32-bit data format, no swizzle) and the non-temporal bit of a buffer instruction's cache policy
 #define SOLON_BUFFER_WORD3 0x00020000
 #define SOLON_BUFFER_NT 2
-#define SOLON_SYNC_WORDS 512     // 8 counters 128 bytes apart, one grid-wide counter, one exit counter, one adrift flag
+#define SOLON_SYNC_WORDS 512     // 8 counters 128 bytes apart, one grid-wide counter (top bit: adrift), one exit counter
 
 // Device-side tables of a plan; every pointer points into the plan's single workspace allocation.
 struct solon_dev {
