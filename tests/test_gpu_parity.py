@@ -264,6 +264,36 @@ def test_phase_encoder_with_more_batches_per_group_than_its_table_holds():
         solon.solon_tune("encode_phase_grid", 0)
 
 
+@pytest.mark.parametrize("m,d", [(8, 7_332_000), (10, 7_332_000), (6, 11_173_000), (10, 11_173_960)])
+def test_tiled_encoder_at_the_papers_sizes_equals_the_flat_kernels(m, d):
+    """The launch shapes the tiled phase-separated encoder chooses by itself at the paper's model sizes (P = 100, s = 5): a grid
+    evened out over the positions (895 block-tiles on 2 x 448 blocks, 716 on 2 x 358, 1818 on 4 x 455) and, at the paper's own
+    d, whole positions on the resident grid with the 67 leftover block-tiles and the partial last tile in a flat launch.
+    Same additions in the same order as the flat kernels: identical bits."""
+    P, s = 100, 5
+    plan = solon.Plan(P, s, m, d)
+    cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
+    G = workloads.make_gradients(cfg, DEV, 181, d=d)
+    Za = torch.zeros((P, plan.d_c), dtype=torch.float32, device=DEV)
+    Zb = torch.zeros_like(Za)
+    try:
+        solon.solon_tune("encode_phase", 0)
+        solon.solon_encode(plan, G, Za)
+        solon.solon_tune("encode_phase", -1)
+        solon.solon_encode(plan, G, Zb)
+        torch.cuda.synchronize()
+        assert torch.equal(Za, Zb)
+        # a window against the oracle
+        lo, n = plan.d_c // 3, 2048
+        oplan = so.make_plan(P, s, m)
+        Gw = host(G[:, lo * m:(lo + n) * m])
+        Z_ref = so.encode(oplan, Gw)
+        got = host(Zb[:, lo:lo + n])
+        assert np.abs(got - Z_ref).max() <= 4e-6 * (np.abs(Z_ref).max() + 1e-30)
+    finally:
+        solon.solon_tune("encode_phase", -1)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_store_pacing_only_shapes_timing(dtype):
     """The clock-paced store schedule of the encoder's write phases decides when a store is issued, never what it
