@@ -408,12 +408,13 @@ def test_the_guess_sample_cannot_be_avoided_through_a_fixed_window():
 
 
 @pytest.mark.parametrize("path,P,s,m,d", [("one_pass", 63, 3, 4, 2_000_000), ("one_pass", 42, 2, 2, 1_600_000), ("two_passes", 100, 5, 10, 1_000_010),
-                                          ("two_passes", 31, 2, 3, 600_001)])
+                                          ("two_passes", 31, 2, 3, 600_001), ("auto_one_pass", 63, 3, 4, 22_000_000)])
 def test_locate_decode_equals_two_passes_bitwise_and_reports_failure(path, P, s, m, d):
     """solon_locate_decode against solon_locate + solon_decode: same V, same projections, the same bits in u - through the
     one-pass kernel, whether the guess holds (corruption visible in the sample), fails (invisible: recombination repeated)
     or there is nothing to find, and through the two passes it takes for other m and for plans with idle nodes; a group
-    with more than s corrupted nodes is reported as by solon_locate."""
+    with more than s corrupted nodes is reported as by solon_locate.  The last shape is one where the call chooses the
+    one-pass kernel by itself, on a grid evened out over its rounds (448 of 512 blocks, three rounds)."""
     cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
     plan = solon.Plan(P, s, m, d)
     oplan = so.make_plan(P, s, m)
@@ -426,7 +427,7 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure(path, P, s,
     g0 = oplan.nodes[0].tolist()
     spread = sorted(int(oplan.nodes[g][k]) for g, k in zip(range(min(s, oplan.q)), (1, 0, 2, 0, 1)))
     try:
-        solon.solon_tune("fuse", 1)
+        solon.solon_tune("fuse", -1 if path == "auto_one_pass" else 1)
         solon.solon_tune("fuse_sample", 1024)
         solon.solon_tune("fuse_sample_leading", 1)
         for byz, from_col, redo in (([], 0, 0), (spread, 0, 0), (spread, 2048, None), (g0[:s], 5000, 1)):   # a group's first node is always guessed
@@ -439,8 +440,8 @@ def test_locate_decode_equals_two_passes_bitwise_and_reports_failure(path, P, s,
                 ub.zero_()
                 Vb, rho_b = solon.solon_locate_decode(plan, R, f, ub, want_rho=True)
                 torch.cuda.synchronize()
-                assert plan.query(solon.SOLON_Q_LAST_ONE_PASS) == (1 if path == "one_pass" else 0)
-                if path == "one_pass":
+                assert plan.query(solon.SOLON_Q_LAST_ONE_PASS) == (1 if "one_pass" in path else 0)
+                if "one_pass" in path:
                     assert redo is None or plan.query(solon.SOLON_Q_LAST_REDO) == redo, (byz, from_col)
                 assert Va == Vb == sorted(byz)
                 assert np.allclose(rho_a, rho_b, rtol=1e-12, atol=0)
