@@ -375,15 +375,29 @@ __global__ __launch_bounds__(256) void encode_chunk_kernel(enc_args a, int64_t p
 // loads (that part does not depend on m), parked in LDS, and then each thread picks up the m coefficients of its
 // own chunk and writes one message element per node (coalesced 4-byte stores).  The last tile may be a partial one as
 // long as the row ends on a vector boundary: vectors past the row's end count as zero, chunks past d_c are not written.
-template <int M, typename T, bool NT>
+// RU = rows of the group sum whose loads are in flight together: 2 for a grid that fills the chip; 8 for the launch of a
+// few tiles behind the phase-separated kernel, which is a chain of latencies: that variant loads without branches and keeps
+// the group's tables in LDS (one partial tile of a group of 20 rows: 13.5 -> 10.9 us; on a full grid the same code is 8 - 12 %
+// slower than the plain one).  The additions keep their order either way.
+template <int M, typename T, bool NT, int RU = 2>
 __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t tile0, ENC_TABLE_PARAMS) {
   constexpr int LV = load_traits<T>::LV;
   constexpr int NVEC = 256 * M / LV;          // 16-byte vectors per row and tile
   constexpr int NI = (NVEC + 255) / 256;      // vectors per thread
   __shared__ float ybar[256 * M];
+  __shared__ int s_node[SOLON_MAX_GROUP];
+  __shared__ float s_w[SOLON_MAX_GROUP];
   const int g = blockIdx.y, tid = threadIdx.x;
   const int b0 = bat_off[g], b1 = bat_off[g + 1];
   const int n0 = grp_off[g], n1 = grp_off[g + 1];
+  // small launches: the group's node list and points go to LDS first (read from memory inside the store loop they are two
+  // chained round trips per node, which a few blocks cannot hide)
+  const bool staged = RU > 2 && n1 - n0 <= SOLON_MAX_GROUP;
+  if (staged && tid < n1 - n0) {
+    const int j = grp_nodes[n0 + tid];
+    s_node[tid] = j;
+    s_w[tid] = w[j];
+  }
   const int64_t tile = tile0 + blockIdx.x;
   const T* base = static_cast<const T*>(a.G) + tile * (256 * M);
   float acc[NI][LV];
@@ -396,12 +410,33 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t ti
 #pragma unroll
     for (int e = 0; e < LV; ++e) acc[i][e] = 0.0f;
   }
-#pragma unroll 2
-  for (int k = b0; k < b1; ++k) {  // group sum, in batch order
-    const T* src = base + (int64_t)grp_batches[k] * a.ldg;
+  if constexpr (RU > 2) {
+    // small launches: every thread loads in every round - a vector outside the tile or the row is replaced by the tile's first
+    // one (always inside the row) and not added - so that no branch stands between the loads of successive rows
+    int off[NI];
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
-      if (inside[i]) load_add<NT>(src + (tid + 256 * i) * LV, acc[i]);
+    for (int i = 0; i < NI; ++i) off[i] = inside[i] ? (tid + 256 * i) * LV : 0;
+#pragma unroll RU
+    for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+      const T* src = base + (int64_t)grp_batches[k] * a.ldg;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) {
+        float v[LV];
+#pragma unroll
+        for (int e = 0; e < LV; ++e) v[e] = 0.0f;
+        load_add<NT>(src + off[i], v);  // 0 + x = x exactly
+#pragma unroll
+        for (int e = 0; e < LV; ++e) acc[i][e] += inside[i] ? v[e] : 0.0f;
+      }
+    }
+  } else {
+#pragma unroll 2
+    for (int k = b0; k < b1; ++k) {  // group sum, in batch order
+      const T* src = base + (int64_t)grp_batches[k] * a.ldg;
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+        if (inside[i]) load_add<NT>(src + (tid + 256 * i) * LV, acc[i]);
+    }
   }
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
@@ -419,8 +454,8 @@ __global__ __launch_bounds__(256) void encode_tile_kernel(enc_args a, int64_t ti
   float* zbase = a.Z + tile * 256 + tid;
   if (tile * 256 + tid >= a.d_c) return;  // partial last tile
   for (int t = n0; t < n1; ++t) {
-    const int j = grp_nodes[t];
-    const float wj = w[j];
+    const int j = staged ? s_node[t - n0] : grp_nodes[t];
+    const float wj = staged ? s_w[t - n0] : w[j];
     float h = y[M - 1];
 #pragma unroll
     for (int l = M - 2; l >= 0; --l) h = fmaf(h, wj, y[l]);  // Horner in w_j
@@ -558,7 +593,8 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
       const int64_t ntiles = (plan->d % LV == 0 ? (plan->d + 256 * M - 1) / (256 * M) : plan->d / (256 * M)) - tile0;
       if (ntiles > 0) {
         dim3 grid((unsigned)ntiles, (unsigned)q);
-        if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
+        if (ntiles <= 8 && nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true, 8>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
+        else if (nt) hipLaunchKernelGGL((encode_tile_kernel<M, T, true>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
         else hipLaunchKernelGGL((encode_tile_kernel<M, T, false>), grid, dim3(threads), 0, st, a, tile0, ENC_TABLE_ARGS(a));
         SOLON_HIP(hipGetLastError());
         done_chunks = std::min<int64_t>((tile0 + ntiles) * 256, plan->d_c);
