@@ -234,7 +234,8 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
  * (1 = the guess ignores the sample and takes every node as honest: times the repeated recombination), "fuse_spin_limit", "project_xcd_map",
  * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced),
  * "majority_rows" (-1 = solon_decode_majority chooses by size, 0 = flat kernels, 1 = the persistent kernel wherever legal),
- * "majority_rows_grid".
+ * "majority_rows_grid", "solve_basis_table" (0 = the locator wavefront rebuilds the orthonormal polynomials of its consistency test
+ * in every call instead of reading the plan's table).
  * Unknown keys are stored and ignored. */
 int solon_tune(const char* key, int value);
 

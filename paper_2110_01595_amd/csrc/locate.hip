@@ -492,16 +492,12 @@ __device__ __forceinline__ unsigned long long lane_bcast_mask(unsigned long long
   return ((unsigned long long)hi << 32) | lo;
 }
 
-// Orthonormal basis Q (by the three-term recurrence over the points, lane = point), residual r = y - Q Q^T y into
-// S.val, and M = I - Q Q^T into S.A (lane = row).  `n` points, lanes 0 .. n-1.
+// Orthonormal polynomials of degree < m over the points (three-term recurrence, lane = point): q[k] = value of the k-th one at
+// this lane's point, fit = this lane's value of the projection of yc onto them.  One round of wavefront sums per degree.
 template <int MM>  // MM >= m: number of basis polynomials the registers hold
-__device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m, int lane) {
-  const bool pt = lane < n;
-  const int rows = n <= 16 ? 1 : n <= 32 ? 2 : 4;
-  const double wgt = pt ? 1.0 : 0.0;
-  const double yc = fmin(fmax(y, -SOLON_Y_CLAMP), SOLON_Y_CLAMP);
-  double p_cur = 0.0, t = wgt, fit = 0.0;  // t: the polynomial of the current degree before normalisation
-  double q[MM];
+__device__ __forceinline__ void lane_basis(double x, double yc, double wgt, int m, int rows, double (&q)[MM], double& fit) {
+  double p_cur = 0.0, t = wgt;  // t: the polynomial of the current degree before normalisation
+  fit = 0.0;
 #pragma unroll
   for (int k = 0; k < MM; ++k) q[k] = 0.0;
 #pragma unroll
@@ -518,6 +514,37 @@ __device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m,
       p_cur = p_new;
     }
   }
+}
+
+// Orthonormal basis Q, residual r = y - Q Q^T y into S.val, and M = I - Q Q^T into S.A (lane = row).  `n` points, lanes
+// 0 .. n-1.  The basis depends on the points alone, so a plan keeps it in a table (`qrow`: this lane's row of it, or null when
+// there is no table or some point of the group dropped out as non-finite); with it the m dependent rounds of sums shrink to
+// ceil(m / 4) independent ones for the projection of y.
+template <int MM>
+__device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m, int lane, const double* qrow, bool have_table) {
+  const bool pt = lane < n;
+  const int rows = n <= 16 ? 1 : n <= 32 ? 2 : 4;
+  const double yc = fmin(fmax(y, -SOLON_Y_CLAMP), SOLON_Y_CLAMP);
+  double q[MM], fit;
+  if (have_table) {
+#pragma unroll
+    for (int k = 0; k < MM; ++k) q[k] = (pt && k < m) ? qrow[k] : 0.0;
+    fit = 0.0;
+#pragma unroll
+    for (int k0 = 0; k0 < MM; k0 += 4) {
+      if (k0 < m) {  // wave-uniform
+        double v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = k0 + e < MM ? yc * q[k0 + e] : 0.0;
+        wave_sums<4>(v, rows);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (k0 + e < MM) fit = fma(v[e], q[k0 + e], fit);
+      }
+    }
+  } else {
+    lane_basis<MM>(x, yc, pt ? 1.0 : 0.0, m, rows, q, fit);
+  }
   __syncthreads();  // S.A, S.val are free again
 #pragma unroll
   for (int k = 0; k < MM; ++k) S.Q[lane][k] = q[k];
@@ -530,6 +557,41 @@ __device__ void lane_test_setup(solve_smem& S, double x, double y, int n, int m,
     S.A[lane][j] = acc;
   }
   __syncthreads();
+}
+
+// The table of lane_test_setup for every group of a plan: qtab[position in grp_nodes][k], one wavefront per group.
+__global__ __launch_bounds__(64) void basis_table_kernel(const int32_t* __restrict__ grp_off, const int32_t* __restrict__ grp_nodes,
+                                                         const float* __restrict__ w, int m, double yc0, double* __restrict__ qtab) {
+  const int g = blockIdx.x, lane = threadIdx.x;
+  const int n0 = grp_off[g], n = grp_off[g + 1] - n0;
+  if (n > 64) return;  // wave-uniform
+  const bool pt = lane < n;
+  const double x = pt ? (double)w[grp_nodes[n0 + lane]] : 0.0;
+  const int rows = n <= 16 ? 1 : n <= 32 ? 2 : 4;
+  double q[SOLON_MAX_M], fit;
+  // the same instantiation as the solve wavefront takes for this m (yc0 = 0 arrives as an argument, so nothing is folded away)
+  if (m <= 4) {
+    double q4[4];
+    lane_basis<4>(x, yc0, pt ? 1.0 : 0.0, m, rows, q4, fit);
+#pragma unroll
+    for (int k = 0; k < SOLON_MAX_M; ++k) q[k] = k < 4 ? q4[k < 4 ? k : 0] : 0.0;
+  } else if (m <= 8) {
+    double q8[8];
+    lane_basis<8>(x, yc0, pt ? 1.0 : 0.0, m, rows, q8, fit);
+#pragma unroll
+    for (int k = 0; k < SOLON_MAX_M; ++k) q[k] = k < 8 ? q8[k < 8 ? k : 0] : 0.0;
+  } else if (m <= 12) {
+    double q12[12];
+    lane_basis<12>(x, yc0, pt ? 1.0 : 0.0, m, rows, q12, fit);
+#pragma unroll
+    for (int k = 0; k < SOLON_MAX_M; ++k) q[k] = k < 12 ? q12[k < 12 ? k : 0] : 0.0;
+  } else {
+    lane_basis<SOLON_MAX_M>(x, yc0, pt ? 1.0 : 0.0, m, rows, q, fit);
+  }
+  if (pt) {
+#pragma unroll
+    for (int k = 0; k < SOLON_MAX_M; ++k) qtab[(int64_t)(n0 + lane) * SOLON_MAX_M + k] = q[k];
+  }
 }
 
 // One lane's verdict on one candidate set `mask` (bits = points) of at most E points.
@@ -612,6 +674,8 @@ __device__ bool wave_test(double x, double y, int n, int m, unsigned long long m
 struct test_ctx {
   double x, y;  // this lane's point (compacted position = lane)
   int n, m, se, lane;
+  const double* qrow;  // this lane's row of the plan's basis table, when have_table
+  bool have_table;     // wave-uniform: the table exists and every point of the group is finite
 };
 
 // Verdicts on the candidate sets of the lanes with `active` set: bit l = lane l's set explains the group.  Locator
@@ -673,10 +737,10 @@ __device__ unsigned long long search_located_set(solve_smem& S, const test_ctx& 
   if (pt) S.by_rank[drank] = lane;
   __syncthreads();
   if (se <= SOLON_LANE_TEST_MAX) {
-    if (c.m <= 4) lane_test_setup<4>(S, c.x, c.y, n, c.m, lane);
-    else if (c.m <= 8) lane_test_setup<8>(S, c.x, c.y, n, c.m, lane);
-    else if (c.m <= 12) lane_test_setup<12>(S, c.x, c.y, n, c.m, lane);
-    else lane_test_setup<SOLON_MAX_M>(S, c.x, c.y, n, c.m, lane);
+    if (c.m <= 4) lane_test_setup<4>(S, c.x, c.y, n, c.m, lane, c.qrow, c.have_table);
+    else if (c.m <= 8) lane_test_setup<8>(S, c.x, c.y, n, c.m, lane, c.qrow, c.have_table);
+    else if (c.m <= 12) lane_test_setup<12>(S, c.x, c.y, n, c.m, lane, c.qrow, c.have_table);
+    else lane_test_setup<SOLON_MAX_M>(S, c.x, c.y, n, c.m, lane, c.qrow, c.have_table);
   }
   // 1. the leading roots of the locator: lane e <= se leaves out the e first points of the |D| order.  The lanes after
   // them (one candidate set per lane) already try each of those sets with one of its points but the last put back -
@@ -763,6 +827,7 @@ struct solve_args {
   const int32_t* grp_nodes;
   const float* w;
   const double* rho;
+  const double* qtab;         // [n_active][SOLON_MAX_M] orthonormal basis of every group's points (basis_table_kernel), or null
   int32_t* vmask;
   int32_t* status;
   int32_t* dec_rows;
@@ -869,6 +934,8 @@ __global__ __launch_bounds__(64) void solve_kernel(solve_args a) {
         // V: the smallest set of points without which the rest is consistent (leading roots first, then wider)
         test_ctx tc;
         tc.x = wl; tc.y = yl; tc.n = nfin; tc.m = m; tc.se = se; tc.lane = lane;
+        tc.have_table = a.qtab != nullptr && nnonfin == 0;  // all points finite: compacted position = position in the group
+        tc.qrow = tc.have_table && pt ? a.qtab + (int64_t)(n0 + lane) * SOLON_MAX_M : nullptr;
         if (se == 0 && pt) drank = lane;
         bool consistent = false;
         const unsigned long long flag_mask = search_located_set(S, tc, drank, a.mode == SOLVE_SPECULATE ? SOLON_SPEC_SEARCH_LIMIT : SOLON_SEARCH_LIMIT, &consistent);
@@ -958,6 +1025,7 @@ int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, 
   a.s = plan->s; a.m = plan->m; a.mode = mode;
   a.blind = mode == SOLVE_SPECULATE && solon_tuning("fuse_blind_guess", 0) != 0;
   a.grp_off = D.grp_off; a.grp_nodes = D.grp_nodes; a.w = D.w; a.rho = D.rho;
+  a.qtab = solon_tuning("solve_basis_table", 1) != 0 ? D.qtab : nullptr;
   a.vmask = D.vmask; a.status = D.status; a.redo = D.redo;
   a.guess_rows = nullptr;
   a.order = D.spec_order;
@@ -968,6 +1036,13 @@ int solon_launch_solve_on(const solon_plan* plan, const solon_dev& D, int mode, 
     a.mode = SOLVE_LOCATE; a.guess_rows = D.spec_rows;
   }
   hipLaunchKernelGGL(solve_kernel, dim3(plan->q), dim3(64), 0, st, a);
+  SOLON_HIP(hipGetLastError());
+  return SOLON_OK;
+}
+
+int solon_launch_basis_table(const solon_plan* plan, const solon_dev& D, hipStream_t st) {
+  if (!D.qtab || plan->q < 1) return SOLON_OK;
+  hipLaunchKernelGGL(basis_table_kernel, dim3(plan->q), dim3(64), 0, st, D.grp_off, D.grp_nodes, D.w, plan->m, 0.0, D.qtab);
   SOLON_HIP(hipGetLastError());
   return SOLON_OK;
 }

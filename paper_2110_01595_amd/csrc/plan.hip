@@ -275,6 +275,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   const size_t o_scoef = take(sizeof(float) * q * m * m);
   const size_t o_redo = take(sizeof(int32_t));
   const size_t o_sorder = take(sizeof(int32_t) * std::max(1, p->n_active));
+  const size_t o_qtab = take(sizeof(double) * SOLON_MAX_M * std::max(1, p->n_active));
   p->ws_bytes = off;
   hipError_t e = hipMalloc(&p->ws, p->ws_bytes);
   if (e != hipSuccess) {
@@ -298,6 +299,7 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
   p->dev.spec_coef = (float*)(base + o_scoef);
   p->dev.redo = (int32_t*)(base + o_redo);
   p->dev.spec_order = (int32_t*)(base + o_sorder);
+  p->dev.qtab = (double*)(base + o_qtab);
   p->pinned_bytes = align_up(sizeof(double) * P + sizeof(int32_t) * (P + q), 256);
   e = hipHostMalloc(&p->pinned, p->pinned_bytes, hipHostMallocDefault);
   if (e != hipSuccess) {
@@ -317,6 +319,13 @@ extern "C" int solon_plan_create(solon_plan** out, int P, int B, int s, int m, i
     (void)hipHostFree(p->pinned);
     delete p;
     return solon_hip_fail(le, "workspace initialisation");
+  }
+  if (solon_launch_basis_table(p, p->dev, nullptr) != SOLON_OK || hipDeviceSynchronize() != hipSuccess) {
+    hipError_t le = hipGetLastError();
+    (void)hipFree(p->ws);
+    (void)hipHostFree(p->pinned);
+    delete p;
+    return solon_hip_fail(le, "basis tables");
   }
   (void)solon_static_prepare();  // set-up of solon_locate_static on this device; a failure is reported by that call itself
   *out = p;

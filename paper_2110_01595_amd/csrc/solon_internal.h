@@ -35,6 +35,7 @@ struct solon_dev {
   float* spec_coef;      // [q][m][m] their coefficient table
   int32_t* spec_order;   // [n_active] every group's nodes with the guessed rows first (both parts ascending)
   int32_t* redo;         // [1] 1 = the guess was wrong, the recombination has to run again
+  double* qtab;          // [n_active][SOLON_MAX_M] orthonormal polynomials over every group's points (the consistency test's basis), or null
 };
 
 struct solon_plan {
@@ -86,6 +87,8 @@ int solon_project_reduce(solon_plan* plan, int ntiles, hipStream_t st);
 // writes the guess tables only); phi that also raises the redo flag when its rows differ from the guess
 enum { SOLVE_TABLES = 0, SOLVE_LOCATE = 1, SOLVE_SPECULATE = 2, SOLVE_LOCATE_CHECK = 3 };
 int solon_launch_solve(solon_plan* plan, int mode, hipStream_t st);
+// fills D.qtab from the group tables already on the device (once, when a plan is created)
+int solon_launch_basis_table(const solon_plan* plan, const solon_dev& D, hipStream_t st);
 // the same three steps on a table of device buffers other than the plan's own workspace (`max_tiles` = rows of D.partials)
 int solon_project_partials_on(const solon_plan* plan, const solon_dev& D, int max_tiles, const float* R, int64_t ldr, const float* f,
                               int64_t ncols, int tile_base, int* ntiles, hipStream_t st, int64_t sample_of = 0);

@@ -48,16 +48,24 @@ def test_rounds_with_a_weak_corruption_behind_an_honest_root(base, attack, P, s,
 
 @pytest.mark.parametrize("P,s,m", GROUP_SHAPES)
 def test_located_set_equals_bruteforce_over_seeds(P, s, m):
+    """Both ways the locator wavefront gets the orthonormal polynomials of its consistency test - from the table a plan holds, and
+    rebuilt in the call (what it does anyway when a point dropped out as non-finite, or without a plan workspace) - name the
+    planted set, as brute force does."""
     wrong = []
-    for n in range(48):
-        base, attack = RECIPES[n % len(RECIPES)]
-        n_byz = s if (n // len(RECIPES)) % 2 == 0 else (n // (2 * len(RECIPES))) % (s + 1)
-        print("round", base, attack, (P, s, m), "seed", n, "corrupted", n_byz, flush=True)
-        plan, R, f, byz = one_group_inputs(base, attack, P, s, m, 512 * m, n, n_byz)
-        V, _ = hip_located(plan, R, f)
-        V_bf = oracle_located(plan, so.project(R, f), "bruteforce_stacked")
-        if not (V == V_bf == byz):
-            wrong.append((n, base, byz, V, V_bf))
+    try:
+        for n in range(48):
+            base, attack = RECIPES[n % len(RECIPES)]
+            n_byz = s if (n // len(RECIPES)) % 2 == 0 else (n // (2 * len(RECIPES))) % (s + 1)
+            print("round", base, attack, (P, s, m), "seed", n, "corrupted", n_byz, flush=True)
+            plan, R, f, byz = one_group_inputs(base, attack, P, s, m, 512 * m, n, n_byz)
+            V_bf = oracle_located(plan, so.project(R, f), "bruteforce_stacked")
+            for table in (1, 0):
+                solon.solon_tune("solve_basis_table", table)
+                V, _ = hip_located(plan, R, f)
+                if not (V == V_bf == byz):
+                    wrong.append((n, base, byz, V, V_bf, table))
+    finally:
+        solon.solon_tune("solve_basis_table", 1)
     assert not wrong, wrong
 
 
