@@ -94,3 +94,26 @@ def test_null_arguments_are_rejected_not_dereferenced():
     v = ctypes.c_int64()
     assert L.solon_plan_query(None, 0, ctypes.byref(v)) == solon.SOLON_E_INVAL
     L.solon_plan_destroy(None)
+
+
+@pytest.mark.parametrize("name,enc,loc,dec", [("C2", 1.008, 0.358, 0.179), ("C3", 4.762, 1.638, 0.614), ("C4", 39.060, 7.936, 3.472),
+                                               ("C5", 37.200, 12.524, 3.968), ("X1", 4.917, 0.451, 0.268)])
+def test_bench_counts_the_bytes_the_method_must_move(name, enc, loc, dec):
+    """bench.py's numerators, in GB, against the figures worked out by hand from the cost analysis (Sec. 3.4, complexity of the
+    encoder and decoder): every gradient read once and every message written once (P d b + P d_c 4), every message and f read
+    once by the projection (P d_c 4 + d_c 4), q m rows recombined into u (q m d_c 4 + d 4).  The one-pass call moves R, f and u
+    once plus the sample behind its guess."""
+    import bench
+    import workloads
+
+    cfg = workloads.CONFIGS[name]
+    plan = solon.Plan(cfg["P"], cfg["s"], cfg["m"], cfg["d"], dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
+    ab = bench.algorithmic_bytes(cfg, plan)
+    assert round(ab["encode"] / 1e9, 3) == enc and round(ab["locate"] / 1e9, 3) == loc and round(ab["decode"] / 1e9, 3) == dec
+    assert ab["total"] == ab["encode"] + ab["locate"] + ab["decode"]
+    two = bench.moved_bytes(cfg, plan, False)
+    assert two["total"] == ab["total"]
+    one = bench.moved_bytes(cfg, plan, True)
+    saved = ab["total"] - one["total"]
+    sample = (cfg["P"] + 1) * min(plan.d_c, 1 << 17) * 4
+    assert saved == plan.q * cfg["m"] * plan.d_c * 4 - sample        # the second read of psi's rows, less the sample projection
