@@ -435,6 +435,69 @@ def sweep_two_streams(steps, warmup):
         torch.cuda.empty_cache()
 
 
+def sweep_graph(steps, warmup):
+    """A step (solon_encode + solon_locate_decode) launched eagerly and replayed from a HIP graph captured once: what the gaps
+    between the six to nine launches of a step cost at the small shapes."""
+    import torch
+
+    import paper_2110_01595_amd as solon
+    import workloads
+
+    dev = torch.device("cuda:0")
+    shapes = [(n, workloads.CONFIGS[n], workloads.seeds(n)) for n in ("C2", "C3", "X1")]
+    shapes.append(("LSTM_P100_s5_m10", dict(P=100, s=5, m=10, d=7_332_000, dtype="f32", dist="normal", sigma=0.01, attack="paper"), dict(G=1, f=2, byz=3, attack=4)))
+    shapes.append(("C5", workloads.CONFIGS["C5"], workloads.seeds("C5")))
+    for name, cfg, sd in shapes:
+        P, s, m, d = cfg["P"], cfg["s"], cfg["m"], cfg["d"]
+        plan = solon.Plan(P, s, m, d, dtype=solon.SOLON_BF16 if cfg["dtype"] == "bf16" else solon.SOLON_F32)
+        d_c = plan.d_c
+        G = workloads.make_gradients(cfg, dev, sd["G"])
+        ld = (d_c + 63) // 64 * 64
+        Z = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
+        R = torch.empty((P, ld), dtype=torch.float32, device=dev)[:, :d_c]
+        u = torch.empty(d, dtype=torch.float32, device=dev)
+        f = workloads.make_projection(d_c, dev, sd["f"])
+        byz = workloads.pick_byzantine(P, s, sd["byz"])
+        solon.solon_encode(plan, G, Z)
+        R.copy_(Z)
+        workloads.apply_attack(R, byz, cfg["attack"], sd["attack"])
+
+        def step():
+            solon.solon_encode(plan, G, Z)
+            solon.solon_locate_decode(plan, R, f, u, want_host=False)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        eager = (time.perf_counter() - t0) * 1e3 / steps
+        u_eager = u.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        replay = (time.perf_counter() - t0) * 1e3 / steps
+        ab = algorithmic_bytes(cfg, plan)
+        print(json.dumps(dict(workload=name, ms_per_step=dict(eager=eager, graph_replay=replay), speedup=eager / replay,
+                              pct_of_peak={k: ab["total"] / (v * 1e-3) / 1e9 / PEAK_HBM_GBS * 100 for k, v in (("eager", eager), ("graph_replay", replay))},
+                              same_u=bool(torch.equal(u, u_eager)), status_ok=solon.solon_decode_status(plan) == 0)), flush=True)
+        del G, Z, R, u, f, graph
+        torch.cuda.empty_cache()
+
+
 def sweep_repetition(steps, warmup):
     """m = 1 (repetition code): the general locate + decode path next to the majority-vote decoder, same inputs."""
     import torch
@@ -499,11 +562,11 @@ def main():
     ap.add_argument("--two-pass", action="store_true", help="time solon_locate + solon_decode instead of solon_locate_decode")
     ap.add_argument("--tune", action="append", default=[], metavar="KEY=INT",
                     help="launch-shape knob passed to solon_tune before the run (measurement aid; may be repeated)")
-    ap.add_argument("--sweep", choices=["paper", "repetition", "conditioning", "two_streams"], default=None,
+    ap.add_argument("--sweep", choices=["paper", "repetition", "conditioning", "two_streams", "graph"], default=None,
                     help="instead of the headline line: 'paper' runs the paper's cost-study shapes, 'repetition' compares the "
                          "m = 1 majority-vote decoder with the general path, 'conditioning' takes the compression ratio up to "
                          "16 and records where located set and decode error leave the bar, 'two_streams' times two independent rounds on one "
-                         "stream and on two; one JSON line per shape")
+                         "stream and on two, 'graph' a step launched eagerly and replayed from a HIP graph; one JSON line per shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run one plain device copy of 4 GiB (reads 4 GiB, writes 4 GiB): the dispatch whose rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels")
@@ -538,6 +601,9 @@ def main():
         return
     if args.sweep == "two_streams":
         sweep_two_streams(args.steps, args.warmup)
+        return
+    if args.sweep == "graph":
+        sweep_graph(args.steps, args.warmup)
         return
 
     main_res, cpu = run_config(args.config, args.steps, args.warmup, not args.no_cpu_baseline, two_pass=args.two_pass)
