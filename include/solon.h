@@ -109,8 +109,10 @@ int solon_default_points(int r_g, float* out);
  *   Z   device, P rows x d_c fp32, row stride ldz elements (ldz >= d_c); rows of idle nodes are not written
  * Coordinates c >= d of the last chunk count as zero.  Group sums and the Horner evaluation are fp32.
  * Large inputs run on a persistent grid whose blocks align their read and write phases through counters in the
- * plan's workspace (so do solon_decode, solon_locate_decode and solon_decode_majority): overlapping two such calls of
- * ONE plan on different streams stays correct (every wait is bounded) but loses that alignment, i.e. runs slower.
+ * plan's workspace (so do solon_decode, solon_locate_decode and solon_decode_majority): overlapping two such calls on
+ * different streams - of one plan or of two, since each of these grids is sized to fill the chip - stays correct (every wait
+ * is bounded, and after the first wait that runs into the bound a launch stops waiting altogether) but loses that
+ * alignment, i.e. runs like the flat kernels.
  */
 int solon_encode(const solon_plan* plan, const void* G, int64_t ldg, float* Z, int64_t ldz, void* hip_stream);
 
