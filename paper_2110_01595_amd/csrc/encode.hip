@@ -141,9 +141,9 @@ template <typename T> struct phase_units;
 template <> struct phase_units<float> { static constexpr int U = 10; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 5; };
 
-// The phase-separated kernels are chosen for rows of G of at least this many bytes whose groups read at least that
+// The tiled phase-separated kernel is chosen for rows of G of at least this many bytes whose groups read at least that
 // many bytes (measured, P = 100: rows of 29 MB in groups of 14 encode 6 to 14 % faster than with the flat kernels,
-// rows of 24 MB equally fast; P = 15: 45 MB rows in groups of 5, 224 MB, 7 % slower)
+// rows of 24 MB equally fast); the one-unit-per-thread kernel has a rule of its own at its launch
 #define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)24 << 20)
 #define SOLON_PHASE_MIN_GROUP_BYTES ((int64_t)320 << 20)
 static bool phase_pays(const solon_plan* plan, int64_t row_bytes) {
@@ -518,7 +518,17 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
         phase_grid = solon_resident_grid((const void*)encode_phase_kernel<M, T>, 1024);
         const int grid_cap = solon_tuning("encode_phase_grid", 0);  // tests: a few blocks make many phases of a small input
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-        if (want_phase < 0 && !phase_pays(plan, nunits * 16)) phase_grid = 0;
+        if (want_phase < 0 && phase_grid > 0) {
+          // Measured (P = 15 ... 100, fp32 and bf16, rows of 15 ... 170 MB): what decides is how many row-phases of work a group
+          // holds - a thread takes U units of a row per phase, the chip `cap` bytes - not the bytes as such: from about four
+          // (fp32: 336 MB per group, bf16: 168 MB) the phase-separated kernel is 3 - 15 % faster than the flat one, below
+          // about three it is 5 - 7 % slower; and two phases per group of which the second is 7 % filled lose 5 % (22 % filled: 9 % faster).
+          const int64_t cap = (int64_t)phase_grid * 1024 * phase_units<T>::U;       // units of a row per phase
+          const int64_t rows = plan->B / plan->q;
+          const int64_t nph = (nunits + cap - 1) / cap;
+          const bool ragged_pair = nph == 2 && 8 * (nunits - cap) < cap;
+          if (nunits * rows < 4 * cap || 7 * nunits < 2 * cap || ragged_pair) phase_grid = 0;
+        }
         if ((int64_t)phase_grid * 1024 * 16 >= ((int64_t)1 << 32)) phase_grid = 0;  // the kernel's 32-bit byte offsets inside a span
       }
       if (phase_grid > 0) {
