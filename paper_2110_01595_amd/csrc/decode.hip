@@ -208,7 +208,12 @@ static int recombine_dispatch(const solon_plan* plan, const float* R, int64_t ld
       phase_grid = solon_resident_grid((const void*)recombine_phase_kernel<M>, 1024);
       const int grid_cap = solon_tuning("decode_phase_grid", 0);
       if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
-      if (want_phase < 0 && punits < 4 * (int64_t)phase_grid * 1024 * recombine_phase_units(M)) phase_grid = 0;  // measured: no gain below four phases
+      // Measured against the flat kernel (P = 15 ... 100, d up to 124 M): m = 4 (24 - 28 rows read) gains 5 - 7 % from three
+      // phases of work on and loses up to 15 % below; m = 1 (9 rows) gains 3 - 8 % from one and a half phases on; m = 2
+      // (6 - 10 rows, 8-byte loads) loses 6 - 22 % at every size tried, up to six phases, and stays with the flat kernel.
+      const int64_t per_phase = (int64_t)phase_grid * 1024 * recombine_phase_units(M);
+      const int64_t min_half_phases = M == 1 ? 3 : M == 4 ? 6 : (int64_t)1 << 40;
+      if (want_phase < 0 && 2 * punits < min_half_phases * per_phase) phase_grid = 0;
     }
     if (phase_grid > 0) {
       hipLaunchKernelGGL((recombine_phase_kernel<M>), dim3((unsigned)phase_grid), dim3(1024), 0, st, R, ldr, plan->q, plan->dev.dec_rows,
