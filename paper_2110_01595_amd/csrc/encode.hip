@@ -141,15 +141,6 @@ template <typename T> struct phase_units;
 template <> struct phase_units<float> { static constexpr int U = 10; };
 template <> struct phase_units<uint16_t> { static constexpr int U = 5; };
 
-// The tiled phase-separated kernel is chosen for rows of G of at least this many bytes whose groups read at least that
-// many bytes (measured, P = 100: rows of 29 MB in groups of 14 encode 6 to 14 % faster than with the flat kernels,
-// rows of 24 MB equally fast); the one-unit-per-thread kernel has a rule of its own at its launch
-#define SOLON_PHASE_MIN_ROW_BYTES ((int64_t)24 << 20)
-#define SOLON_PHASE_MIN_GROUP_BYTES ((int64_t)320 << 20)
-static bool phase_pays(const solon_plan* plan, int64_t row_bytes) {
-  return row_bytes >= SOLON_PHASE_MIN_ROW_BYTES && row_bytes * (plan->B / plan->q) >= SOLON_PHASE_MIN_GROUP_BYTES;
-}
-
 // block-tiles per block and phase of the tiled phase-separated kernel: as many as keep the sums within `budget`
 // registers.  32 gives the faster code; 40 is used where it saves a phase per group.
 constexpr int tile_phase_tiles(int sums_per_tile, int budget) { return budget / sums_per_tile > 0 ? budget / sums_per_tile : 1; }
@@ -564,6 +555,7 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
           (void)hipGetLastError();
         const int grid_cap = solon_tuning("encode_phase_grid", 0);
         if (grid_cap > 0) phase_grid = std::min(phase_grid, grid_cap);
+        const int resident = phase_grid;
         if (phase_grid > 0) {
           // a last position that only a few blocks would work on (the others idle through it) goes to the flat kernel
           if (ptiles >= phase_grid && (ptiles % phase_grid) * 8 < ptiles) phase_tiles = ptiles - ptiles % phase_grid;
@@ -583,7 +575,10 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
           const int64_t per_phase = (int64_t)phase_grid * (wide ? UT40 : UT32);
           if (want_phase < 0) {
             const int64_t rest = phase_tiles % per_phase;
-            if (!phase_pays(plan, plan->d * (int64_t)sizeof(T))) phase_grid = 0;
+            // Measured (P = 30 ... 100, m = 3, 6, 10, fp32 and bf16, rows of 11 ... 150 MB): the phase-separated kernel is 1 - 15 %
+            // faster than the flat one from about 1.8 block-tiles per resident block on (two nearly full positions) and 2 - 25 %
+            // slower below, whatever the bytes (m = 10, fp32: 969 block-tiles + 10 %, 716 - 2 %, 615 - 10 %).
+            if (ptiles * 5 < (int64_t)resident * 9) phase_grid = 0;
             else if (phase_tiles > per_phase && phase_tiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
           }
         }

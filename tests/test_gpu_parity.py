@@ -266,10 +266,10 @@ def test_phase_encoder_with_more_batches_per_group_than_its_table_holds():
 
 @pytest.mark.parametrize("m,d", [(8, 7_332_000), (10, 7_332_000), (6, 11_173_000), (10, 11_173_960)])
 def test_tiled_encoder_at_the_papers_sizes_equals_the_flat_kernels(m, d):
-    """The launch shapes the tiled phase-separated encoder chooses by itself at the paper's model sizes (P = 100, s = 5): a grid
-    evened out over the positions (895 block-tiles on 2 x 448 blocks, 716 on 2 x 358, 1818 on 4 x 455) and, at the paper's own
-    d, whole positions on the resident grid with the 67 leftover block-tiles and the partial last tile in a flat launch.
-    Same additions in the same order as the flat kernels: identical bits."""
+    """The launch shapes of the tiled phase-separated encoder at the paper's model sizes (P = 100, s = 5), on the grid it sizes
+    for itself: evened out over the positions (895 block-tiles on 2 x 448 blocks, 716 on 2 x 358, 1818 on 4 x 455) and, at
+    the paper's own d, whole positions on the resident grid with the 67 leftover block-tiles and the partial last tile in a
+    flat launch.  Same additions in the same order as the flat kernels: identical bits."""
     P, s = 100, 5
     plan = solon.Plan(P, s, m, d)
     cfg = dict(P=P, d=d, dtype="f32", dist="normal", sigma=0.01)
@@ -279,10 +279,12 @@ def test_tiled_encoder_at_the_papers_sizes_equals_the_flat_kernels(m, d):
     try:
         solon.solon_tune("encode_phase", 0)
         solon.solon_encode(plan, G, Za)
-        solon.solon_tune("encode_phase", -1)
-        solon.solon_encode(plan, G, Zb)
-        torch.cuda.synchronize()
-        assert torch.equal(Za, Zb)
+        for mode in (1, -1):                              # the persistent kernel wherever legal; whatever the call chooses
+            solon.solon_tune("encode_phase", mode)
+            Zb.zero_()
+            solon.solon_encode(plan, G, Zb)
+            torch.cuda.synchronize()
+            assert torch.equal(Za, Zb), mode
         # a window against the oracle
         lo, n = plan.d_c // 3, 2048
         oplan = so.make_plan(P, s, m)
