@@ -235,6 +235,7 @@ int solon_decode_status(solon_plan* plan, void* hip_stream);
  * columns instead of tiles at positions hashed from f: lets a test keep a corruption out of the sample), "fuse_blind_guess"
  * (1 = the guess ignores the sample and takes every node as honest: times the repeated recombination), "fuse_spin_limit", "project_xcd_map",
  * "store_pace_gbps" (rate of the store schedule in the encoder's write phases, GB/s; 0 = stores are not paced),
+ * "store_pace_always" (1 = the schedule also runs where the launcher would leave it out: one partly filled phase per group),
  * "majority_rows" (-1 = solon_decode_majority chooses by size, 0 = flat kernels, 1 = the persistent kernel wherever legal),
  * "majority_rows_grid", "solve_basis_table" (0 = the locator wavefront rebuilds the orthonormal polynomials of its consistency test
  * in every call instead of reading the plan's table).
