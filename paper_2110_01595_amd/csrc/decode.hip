@@ -265,8 +265,11 @@ int solon_launch_recombine_from(const solon_plan* plan, const float* R, int64_t 
 
 int solon_launch_recombine(const solon_plan* plan, const float* R, int64_t ldr, float* u, const int32_t* run_flag, hipStream_t st, float step,
                            int update) {
-  if (plan->m == 4) {  // chunks per thread: two measured best on C4 / C5 (0.68 vs 0.70 ms with one, 0.95 ms with four)
-    const int ch = solon_tuning("decode_ch", 2);
+  if (plan->m == 4) {
+    // chunks per thread of the flat kernel: two measured best on large inputs (C4 / C5: 0.68 vs 0.70 ms with one, 0.95 ms with
+    // four; 616 MB of rows: 118 vs 123 us), one on small ones (205 MB: 34.5 vs 41.8 us; 240 MB: 47 vs 60; 313 MB: 55.5 vs 60.5)
+    int ch = solon_tuning("decode_ch", 0);
+    if (ch != 1 && ch != 2 && ch != 4) ch = (int64_t)plan->q * plan->m * plan->d_c * 4 >= ((int64_t)450 << 20) ? 2 : 1;
     if (ch == 4) return recombine_dispatch<4, 4>(plan, R, ldr, u, run_flag, st, step, update);
     if (ch == 2) return recombine_dispatch<4, 2>(plan, R, ldr, u, run_flag, st, step, update);
   }
