@@ -580,9 +580,10 @@ static int encode_dispatch(const solon_plan* plan, const enc_args& a, bool align
           if (want_phase < 0) {
             const int64_t rest = phase_tiles % per_phase;
             // Measured (P = 30 ... 100, m = 3, 6, 10, fp32 and bf16, rows of 11 ... 150 MB): the phase-separated kernel is 1 - 15 %
-            // faster than the flat one from about 1.8 block-tiles per resident block on (two nearly full positions) and 2 - 25 %
-            // slower below, whatever the bytes (m = 10, fp32: 969 block-tiles + 10 %, 716 - 2 %, 615 - 10 %).
-            if (ptiles * 5 < (int64_t)resident * 9) phase_grid = 0;
+            // faster than the flat one from about 1.5 block-tiles per resident block on and 2 - 25 % slower below, whatever the
+            // bytes (512 resident blocks, fp32: m = 10: 969 block-tiles + 10 %, 716 - 2 %, 615 - 10 %; m = 8: 895 and 793 + 4 %; m = 6: 1025
+            // + 9 %, 813 + 2 %, 651 - 15 %).
+            if (ptiles * 2 < (int64_t)resident * 3) phase_grid = 0;
             else if (phase_tiles > per_phase && phase_tiles < 2 * per_phase && rest != 0 && 2 * rest < per_phase) phase_grid = 0;
           }
         }
